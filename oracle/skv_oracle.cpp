@@ -1,0 +1,353 @@
+// CPU ORACLE -- TEST INFRASTRUCTURE ONLY.
+//
+// Plain, slow, obviously-correct statement of what the selective-reuse prefill path
+// computes.  Nothing here is shared with the GPU library: no headers, no helpers, no
+// tables.  Only tests, the smoke check and the benchmark's CPU-baseline leg may load it.
+//
+// What it follows (SafeKV paper):
+//  * Unified radix-tree index with per-entry visibility metadata (Section 4.3.1,
+//    "Unified Privacy-Preserving Cache Index"): a lookup walks the prefix path and checks
+//    private_tag at every hop; a private entry is visible only to its creator_id; the walk
+//    stops at the first entry it may not use.
+//  * Access monitor (Section 4.2.2, "Safeguard"): every cache lookup records, per KV block,
+//    the hit count of the current window (hit_cur) and the number of distinct tenants that
+//    hit it (u_cnt); RDR = u_cnt / hit_cur (also Section 6, "Misclassification Risk and
+//    Exposure Control", the RDR equation).
+//  * Scaled dot-product attention with KV reuse (Section 2.1): cached K/V of the matched
+//    prefix are reused, only the uncached suffix is computed; evaluated here from the
+//    textbook definition in double precision.
+//
+// Readings taken where the paper is silent (block = 16 tokens, metadata per block, child
+// key = whole first block, first insertion of a block-prefix wins, the creator's own hits
+// count) are listed in the design document.
+//
+// Pins: brute-force prefix scans, the 0 % / 100 % sensitive special cases, the visibility
+// invariants, counter conservation, and closed-form / library attention cases, all in the
+// CPU test-suite.  Unpinned: nothing in this file (the RDR *decision* is not implemented here).
+
+#include <array>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <functional>
+#include <map>
+#include <memory>
+#include <set>
+#include <thread>
+#include <vector>
+
+namespace {
+
+constexpr int kBlock = 16;
+using BlockKey = std::array<int32_t, kBlock>;
+
+struct BlockEntry {
+  BlockKey tokens;
+  bool is_private;      // private_tag
+  int32_t creator_id;
+  int32_t page_id;      // KV address of this block (address-vector entry)
+  int64_t block_id;     // caller's index of the block that created this entry
+  uint64_t hit_cur = 0;
+  std::set<int32_t> tenants;  // distinct tenants that hit the block in the current window
+};
+
+struct Node {
+  std::vector<BlockEntry> blocks;               // the compressed edge: one or more blocks
+  std::map<BlockKey, std::unique_ptr<Node>> children;  // keyed by the child's whole first block
+};
+
+struct Tree {
+  Node root;  // holds no blocks
+  int max_node_blocks;  // 0 = unlimited (path-compressed); 1 = one block per node
+  int64_t n_blocks = 0;
+};
+
+BlockKey key_at(const int32_t* tok) {
+  BlockKey k;
+  std::memcpy(k.data(), tok, sizeof(int32_t) * kBlock);
+  return k;
+}
+
+// Cut `node` after its first `keep` blocks; the remainder becomes its only child.
+void split_node(Node* node, size_t keep) {
+  auto tail = std::make_unique<Node>();
+  tail->blocks.assign(node->blocks.begin() + keep, node->blocks.end());
+  tail->children = std::move(node->children);
+  node->children.clear();
+  node->blocks.resize(keep);
+  BlockKey k = tail->blocks[0].tokens;
+  node->children[k] = std::move(tail);
+}
+
+void insert_sequence(Tree* t, const int32_t* tok, int64_t n_blocks, const uint8_t* sens,
+                     const int32_t* owner, const int32_t* page, int64_t first_block_id) {
+  Node* node = &t->root;
+  int64_t j = 0;  // next block of the sequence
+  while (j < n_blocks) {
+    BlockKey k = key_at(tok + j * kBlock);
+    auto it = node->children.find(k);
+    if (it == node->children.end()) {
+      // nothing cached below this point: append the remainder as new entries
+      Node* at = node;
+      while (j < n_blocks) {
+        auto fresh = std::make_unique<Node>();
+        int64_t take = n_blocks - j;
+        if (t->max_node_blocks > 0 && take > t->max_node_blocks) take = t->max_node_blocks;
+        for (int64_t i = 0; i < take; ++i, ++j) {
+          BlockEntry e;
+          e.tokens = key_at(tok + j * kBlock);
+          e.is_private = sens[j] != 0;
+          e.creator_id = owner[j];
+          e.page_id = page[j];
+          e.block_id = first_block_id + j;
+          fresh->blocks.push_back(e);
+          t->n_blocks++;
+        }
+        BlockKey fk = fresh->blocks[0].tokens;
+        Node* next = fresh.get();
+        at->children[fk] = std::move(fresh);
+        at = next;
+      }
+      return;
+    }
+    Node* child = it->second.get();
+    size_t same = 0;  // blocks of the child's edge equal to the sequence
+    while (same < child->blocks.size() && j + (int64_t)same < n_blocks &&
+           child->blocks[same].tokens == key_at(tok + (j + same) * kBlock))
+      ++same;
+    // blocks already present keep their first metadata (first insertion wins)
+    j += same;
+    if (same < child->blocks.size()) {
+      if (j == n_blocks) return;          // sequence ends inside the edge: nothing new
+      split_node(child, same);            // diverges inside the edge
+    }
+    node = child;
+  }
+}
+
+// Longest visible prefix for one request.  Returns matched blocks; fills entries.
+int64_t match_one(Tree* t, const int32_t* tok, int64_t n_tokens, int32_t tenant,
+                  std::vector<BlockEntry*>* out) {
+  const int64_t nb = n_tokens / kBlock;  // a trailing partial block never matches
+  Node* node = &t->root;
+  int64_t j = 0;
+  while (j < nb) {
+    auto it = node->children.find(key_at(tok + j * kBlock));
+    if (it == node->children.end()) return j;
+    Node* child = it->second.get();
+    for (size_t i = 0; i < child->blocks.size(); ++i) {
+      if (j == nb) return j;
+      BlockEntry& e = child->blocks[i];
+      if (!(e.tokens == key_at(tok + j * kBlock))) return j;
+      if (e.is_private && e.creator_id != tenant) return j;   // visibility rule, every hop
+      out->push_back(&e);
+      ++j;
+    }
+    node = child;
+  }
+  return j;
+}
+
+void for_each_block(Node* n, const std::function<void(BlockEntry&)>& f) {
+  for (auto& b : n->blocks) f(b);
+  for (auto& kv : n->children) for_each_block(kv.second.get(), f);
+}
+int64_t count_nodes(Node* n) {
+  int64_t c = 1;
+  for (auto& kv : n->children) c += count_nodes(kv.second.get());
+  return c;
+}
+
+inline double load_elem(const void* base, int dtype, int64_t idx) {
+  if (dtype == 0) return (double)((const float*)base)[idx];
+  uint32_t bits = (uint32_t)((const uint16_t*)base)[idx] << 16;  // bf16 -> fp32, exact
+  float f;
+  std::memcpy(&f, &bits, 4);
+  return (double)f;
+}
+
+struct AttnArgs {
+  int dtype, Hq, Hkv, d;
+  double scale;
+  const int32_t* q_off;
+  const void *q, *knew, *vnew, *kpool, *vpool;
+  const int32_t* matched_len;
+  const int32_t* page_table;
+  int max_blocks;
+};
+
+// One output row: request r, query head h, suffix position i.
+void attention_row(const AttnArgs& a, int r, int h, int i, double* out) {
+  const int d = a.d, G = a.Hq / a.Hkv, hk = h / G;
+  const int64_t L = a.matched_len[r];
+  const int64_t n_keys = L + i + 1;  // whole reused prefix, then own positions 0..i
+  const int64_t qrow = ((int64_t)a.q_off[r] + i) * a.Hq + h;
+  std::vector<double> logit(n_keys);
+  double m = -INFINITY;
+  for (int64_t j = 0; j < n_keys; ++j) {
+    const void* kb;
+    int64_t kidx;
+    if (j < L) {
+      int64_t page = a.page_table[(int64_t)r * a.max_blocks + j / kBlock];
+      kb = a.kpool;
+      kidx = ((page * kBlock + j % kBlock) * a.Hkv + hk) * d;
+    } else {
+      kb = a.knew;
+      kidx = (((int64_t)a.q_off[r] + (j - L)) * a.Hkv + hk) * d;
+    }
+    double s = 0.0;
+    for (int c = 0; c < d; ++c) s += load_elem(a.q, a.dtype, qrow * d + c) * load_elem(kb, a.dtype, kidx + c);
+    logit[j] = a.scale * s;
+    if (logit[j] > m) m = logit[j];
+  }
+  double denom = 0.0;
+  std::vector<double> acc(d, 0.0);
+  for (int64_t j = 0; j < n_keys; ++j) {
+    const double p = std::exp(logit[j] - m);
+    denom += p;
+    const void* vb;
+    int64_t vidx;
+    if (j < L) {
+      int64_t page = a.page_table[(int64_t)r * a.max_blocks + j / kBlock];
+      vb = a.vpool;
+      vidx = ((page * kBlock + j % kBlock) * a.Hkv + hk) * d;
+    } else {
+      vb = a.vnew;
+      vidx = (((int64_t)a.q_off[r] + (j - L)) * a.Hkv + hk) * d;
+    }
+    for (int c = 0; c < d; ++c) acc[c] += p * load_elem(vb, a.dtype, vidx + c);
+  }
+  for (int c = 0; c < d; ++c) out[c] = acc[c] / denom;
+}
+
+}  // namespace
+
+extern "C" {
+
+void* okv_tree_new(int max_node_blocks) {
+  Tree* t = new Tree();
+  t->max_node_blocks = max_node_blocks;
+  return t;
+}
+void okv_tree_free(void* t) { delete (Tree*)t; }
+
+// Insert cached sequences.  seq_off are token offsets (multiples of 16); the per-block arrays
+// are indexed by the block's position in the concatenated input (its "block id").
+int okv_tree_insert(void* tp, int64_t n_seq, const int64_t* seq_off, const int32_t* tokens,
+                    const uint8_t* sens, const int32_t* owner, const int32_t* page) {
+  Tree* t = (Tree*)tp;
+  for (int64_t s = 0; s < n_seq; ++s) {
+    int64_t lo = seq_off[s], hi = seq_off[s + 1];
+    if (lo % kBlock || hi % kBlock || hi < lo) return -1;
+    int64_t b0 = lo / kBlock;
+    insert_sequence(t, tokens + lo, (hi - lo) / kBlock, sens + b0, owner + b0, page + b0, b0);
+  }
+  return 0;
+}
+
+int64_t okv_tree_n_blocks(void* tp) { return ((Tree*)tp)->n_blocks; }
+int64_t okv_tree_n_nodes(void* tp) { return count_nodes(&((Tree*)tp)->root) - 1; }
+
+// Match a batch sequentially.  page_table is [n_req, max_blocks] (-1 beyond the match),
+// block_ids likewise (may be null).  update != 0 records the hits in the access monitor.
+int okv_match(void* tp, int32_t n_req, const int32_t* req_off, const int32_t* req_tokens,
+              const int32_t* req_tenant, int32_t max_blocks, int32_t* matched_len,
+              int32_t* page_table, int64_t* block_ids, int update) {
+  Tree* t = (Tree*)tp;
+  for (int32_t r = 0; r < n_req; ++r) {
+    std::vector<BlockEntry*> hits;
+    int64_t n_tok = req_off[r + 1] - req_off[r];
+    if (n_tok / kBlock > max_blocks) n_tok = (int64_t)max_blocks * kBlock;
+    int64_t k = match_one(t, req_tokens + req_off[r], n_tok, req_tenant[r], &hits);
+    matched_len[r] = (int32_t)(k * kBlock);
+    for (int32_t j = 0; j < max_blocks; ++j) {
+      page_table[(int64_t)r * max_blocks + j] = j < k ? hits[j]->page_id : -1;
+      if (block_ids) block_ids[(int64_t)r * max_blocks + j] = j < k ? hits[j]->block_id : -1;
+    }
+    if (update)
+      for (BlockEntry* e : hits) {
+        e->hit_cur += 1;
+        e->tenants.insert(req_tenant[r]);
+      }
+  }
+  return 0;
+}
+
+// Counters of the current window, indexed by block id; entries of blocks that created no
+// tree entry (repeats of an already cached block-prefix) stay 0.
+void okv_counters(void* tp, int64_t n_in_blocks, uint32_t* hit, uint32_t* u_cnt) {
+  std::memset(hit, 0, sizeof(uint32_t) * n_in_blocks);
+  std::memset(u_cnt, 0, sizeof(uint32_t) * n_in_blocks);
+  for_each_block(&((Tree*)tp)->root, [&](BlockEntry& e) {
+    hit[e.block_id] = (uint32_t)e.hit_cur;
+    u_cnt[e.block_id] = (uint32_t)e.tenants.size();
+  });
+}
+
+// The single tenant recorded for a block, or -1 if none / -2 if several (for the test of the
+// "sensitive block is only ever hit by its owner" property).
+void okv_sole_tenant(void* tp, int64_t n_in_blocks, int32_t* who) {
+  for (int64_t i = 0; i < n_in_blocks; ++i) who[i] = -1;
+  for_each_block(&((Tree*)tp)->root, [&](BlockEntry& e) {
+    who[e.block_id] = e.tenants.empty() ? -1 : (e.tenants.size() == 1 ? *e.tenants.begin() : -2);
+  });
+}
+
+void okv_counters_reset(void* tp) {
+  for_each_block(&((Tree*)tp)->root, [&](BlockEntry& e) {
+    e.hit_cur = 0;
+    e.tenants.clear();
+  });
+}
+
+// Gather: copy the matched pages of K and V into per-request contiguous staging, requests
+// back to back.  elem_bytes * page_elems bytes per page.
+void okv_gather(int64_t page_bytes, int32_t n_req, const int32_t* matched_len,
+                const int32_t* page_table, int32_t max_blocks, const void* kpool,
+                const void* vpool, void* kctx, void* vctx) {
+  int64_t o = 0;
+  for (int32_t r = 0; r < n_req; ++r)
+    for (int32_t j = 0; j < matched_len[r] / kBlock; ++j, ++o) {
+      int64_t p = page_table[(int64_t)r * max_blocks + j];
+      std::memcpy((char*)kctx + o * page_bytes, (const char*)kpool + p * page_bytes, page_bytes);
+      std::memcpy((char*)vctx + o * page_bytes, (const char*)vpool + p * page_bytes, page_bytes);
+    }
+}
+
+// Attention.  dtype 0 = fp32, 1 = bf16 (raw 16-bit).  If n_rows < 0 every (token, head) row is
+// computed into out[sum S][Hq][d]; otherwise the listed rows into out[n_rows][d].
+int okv_attention(int dtype, int Hq, int Hkv, int d, double scale, int32_t n_req,
+                  const int32_t* q_off, const void* q, const void* knew, const void* vnew,
+                  const void* kpool, const void* vpool, const int32_t* matched_len,
+                  const int32_t* page_table, int32_t max_blocks, int64_t n_rows,
+                  const int32_t* row_req, const int32_t* row_head, const int32_t* row_pos,
+                  double* out, int n_threads) {
+  if (Hq % Hkv) return -1;
+  AttnArgs a{dtype, Hq, Hkv, d, scale, q_off, q, knew, vnew, kpool, vpool, matched_len,
+             page_table, max_blocks};
+  std::vector<std::array<int32_t, 3>> rows;
+  if (n_rows < 0) {
+    for (int32_t r = 0; r < n_req; ++r)
+      for (int32_t i = 0; i < q_off[r + 1] - q_off[r]; ++i)
+        for (int32_t h = 0; h < Hq; ++h) rows.push_back({r, h, i});
+  } else {
+    for (int64_t x = 0; x < n_rows; ++x) rows.push_back({row_req[x], row_head[x], row_pos[x]});
+  }
+  auto work = [&](int tid, int nt) {
+    for (size_t x = tid; x < rows.size(); x += nt) {
+      int r = rows[x][0], h = rows[x][1], i = rows[x][2];
+      double* o = n_rows < 0 ? out + (((int64_t)q_off[r] + i) * Hq + h) * d : out + (int64_t)x * d;
+      attention_row(a, r, h, i, o);
+    }
+  };
+  if (n_threads <= 1) {
+    work(0, 1);
+  } else {
+    std::vector<std::thread> th;
+    for (int t = 0; t < n_threads; ++t) th.emplace_back(work, t, n_threads);
+    for (auto& x : th) x.join();
+  }
+  return 0;
+}
+
+}  // extern "C"
