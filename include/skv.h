@@ -1,0 +1,171 @@
+/*
+ * skv.h -- C ABI of the selective-reuse prefill path for AMD MI355X (gfx950).
+ *
+ * The path follows the SafeKV paper's request path (Section 4.1, "System Overview"):
+ * a prefix lookup in the unified radix-tree index with a per-entry visibility check
+ * (Section 4.3.1), the access-monitor update that feeds the RDR safeguard
+ * (Section 4.2.2), reading the reused KV blocks through the entry's address vector
+ * (Section 4.3.2, "Path Compression"), and prefill attention that reuses cached K/V
+ * and computes only the uncached part (Section 2.1).
+ *
+ * Conventions
+ *  - Pointers named d_* are DEVICE pointers (HIP device memory of the current device);
+ *    all other pointers are HOST pointers.  `stream` is a hipStream_t passed as void*
+ *    (NULL = the default stream).
+ *  - The library never allocates or frees device memory.  Every device buffer, including
+ *    the tree slab and the attention workspace, belongs to the caller and must stay valid
+ *    until the work enqueued on `stream` has finished.
+ *  - Calls only enqueue work on `stream` and return; they do not synchronise, except
+ *    skv_tree_build, which returns after its uploads have completed.
+ *  - Every function returns SKV_OK (0) or a negative error code; nothing is enqueued when
+ *    an error is returned.  Arguments that live on the device (offsets, tenants, page ids)
+ *    cannot be validated by the host: kernels clamp or skip values that are out of range
+ *    instead of faulting, as described per function.
+ *  - A tree handle is thread-compatible, not thread-safe: concurrent calls on one tree,
+ *    or overlapping skv_match batches on different streams, race on the counters.
+ *  - A KV block is 16 tokens.  KV pools are [n_pages][16][n_kv_heads][head_dim], row major.
+ */
+#ifndef SKV_H
+#define SKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SKV_OK 0
+#define SKV_EINVAL (-1) /* null pointer, malformed description, unsupported shape   */
+#define SKV_ENOMEM (-2) /* caller-provided slab / workspace too small                */
+#define SKV_ERANGE (-3) /* a value exceeds a built-in limit (e.g. n_tenants > 128)   */
+#define SKV_EHIP (-4)   /* a HIP runtime call failed (see skv_last_hip_error)        */
+
+#define SKV_BLOCK_TOKENS 16
+#define SKV_MAX_TENANTS 128
+
+#define SKV_F32 0
+#define SKV_BF16 1
+
+const char* skv_strerror(int code);
+/* hipError_t of the last failing HIP call on this thread (0 if none). */
+int skv_last_hip_error(void);
+
+typedef struct skv_tree skv_tree; /* opaque host handle; owns host bookkeeping only */
+
+/* Cached side: n_seq token sequences, each a whole number of 16-token blocks, with one
+ * (private_tag, creator_id, KV address) triple per block (Section 4.3.1: every entry
+ * stores private_tag and creator_id).  Per-block arrays are indexed by the block's
+ * position in the concatenation of all sequences (its "input block id"). */
+typedef struct {
+  int32_t block_tokens;         /* must be 16 */
+  int32_t n_tenants;            /* 1 .. 128 */
+  int32_t n_pages;              /* pages in the KV pool; page ids lie in [0, n_pages) */
+  int64_t n_seq;
+  const int64_t* seq_off;       /* host [n_seq+1] token offsets, non-decreasing, multiples of 16 */
+  const int32_t* tokens;        /* host [seq_off[n_seq]] */
+  const uint8_t* blk_sensitive; /* host, per input block: 1 = private, 0 = shareable */
+  const int32_t* blk_owner;     /* host, per input block: creator tenant in [0, n_tenants) */
+  const int32_t* blk_page;      /* host, per input block: page id */
+} skv_tree_desc;
+
+/* Upper bound, in bytes, of the device slab skv_tree_build needs for this description. */
+int skv_tree_build_size(const skv_tree_desc* desc, size_t* device_bytes);
+
+/* Build the index (Section 4.3.1 Insert; Section 4.3.2 path compression): inserts the
+ * sequences in order, where a block whose whole block-prefix is already cached keeps the
+ * first insertion's metadata and page; collapses every non-branching run of blocks into one
+ * node carrying a per-block page-id vector; writes the flattened tree into d_slab (256-byte
+ * aligned, at least skv_tree_build_size bytes) and zeroes the counters.
+ * Errors: SKV_EINVAL for null pointers, block_tokens != 16, offsets that decrease or are not
+ * multiples of 16, an owner outside [0, n_tenants), a page id outside [0, n_pages), the same
+ * page id on two distinct cached blocks, or a misaligned slab; SKV_ERANGE for n_tenants
+ * outside [1, 128] or more than 2^31-1 blocks; SKV_ENOMEM if `bytes` is too small.
+ * Synchronises `stream` before returning. */
+int skv_tree_build(const skv_tree_desc* desc, void* d_slab, size_t bytes, void* stream,
+                   skv_tree** out);
+
+/* n_nodes: compressed nodes (root excluded); n_blocks: distinct cached blocks;
+ * n_in_blocks: blocks in the description (repeats included).  Any pointer may be NULL. */
+int skv_tree_info(const skv_tree* tree, int64_t* n_nodes, int64_t* n_blocks, int64_t* n_in_blocks);
+
+/* Frees the host handle.  The slab stays the caller's. */
+void skv_tree_destroy(skv_tree* tree);
+
+/* Longest visible prefix match + access-monitor update (Section 4.3.1 Search, Section 4.2.2).
+ * For request r with tokens d_req_tokens[d_req_off[r] .. d_req_off[r+1]) and tenant
+ * d_req_tenant[r]: k_r = the largest k <= min(floor(N_r/16), max_blocks) such that the first
+ * k blocks follow a root path of the tree and each of them is shareable or created by that
+ * tenant (the walk stops at the first block that is absent or not visible).
+ * Writes d_matched_len[r] = 16*k_r and d_page_table[r*max_blocks + j] = page id of block j for
+ * j < k_r, -1 for k_r <= j < max_blocks.  For every matched block adds 1 to its hit counter
+ * and records the tenant in its distinct-tenant set (commutative atomics: the batch result
+ * does not depend on execution order).
+ * A request whose tenant is outside [0, n_tenants) or whose offsets decrease matches nothing.
+ * Errors: SKV_EINVAL for null pointers or negative sizes.  n_req == 0 is a no-op. */
+int skv_match(skv_tree* tree, int32_t n_req, const int32_t* d_req_off, const int32_t* d_req_tokens,
+              const int32_t* d_req_tenant, int32_t max_blocks, int32_t* d_matched_len,
+              int32_t* d_page_table, void* stream);
+
+/* Current-window counters per input block id (Section 4.2.2: hit_cur and u_cnt;
+ * RDR = u_cnt / hit_cur): d_hit[b] = hits, d_ucnt[b] = distinct tenants.  Both arrays have
+ * n_in_blocks entries; blocks that repeat an already cached block-prefix read 0. */
+int skv_counters_read(skv_tree* tree, uint32_t* d_hit, uint32_t* d_ucnt, void* stream);
+
+/* Start a new window: zero every block's hit counter and tenant set. */
+int skv_counters_reset(skv_tree* tree, void* stream);
+
+/* Device-side layout of the uncached suffixes: S_r = N_r - matched_len[r];
+ * d_q_off[0] = 0, d_q_off[r+1] = d_q_off[r] + S_r  ([n_req+1], row offsets into Q/K_new/V_new/O). */
+int skv_suffix_offsets(int32_t n_req, const int32_t* d_req_off, const int32_t* d_matched_len,
+                       int32_t* d_q_off, void* stream);
+
+typedef struct {
+  int32_t n_q_heads;
+  int32_t n_kv_heads; /* divides n_q_heads; query head h uses kv head h / (n_q_heads/n_kv_heads) */
+  int32_t head_dim;   /* SKV_BF16: 128;  SKV_F32: 64 or 128 */
+  int32_t dtype;      /* SKV_F32 or SKV_BF16: type of Q, K, V, the pools and the output */
+  float scale;        /* softmax scale, normally 1/sqrt(head_dim) */
+} skv_attn_desc;
+
+/* Gather the reused pages (Section 4.3.2: the lookup reads the required KV blocks directly from
+ * the address vector): request r's k_r matched K pages are copied, in order, to
+ * d_kctx[ctx_off[r] .. ctx_off[r] + 16*k_r) (token rows of n_kv_heads*head_dim elements), same
+ * for V, with ctx_off the exclusive prefix sum of matched_len, which is also written to
+ * d_ctx_off ([n_req+1], int64).  Byte-exact copy.  Pages whose id is outside [0, n_pages) and
+ * rows at or beyond ctx_capacity_tokens are skipped.
+ * Errors: SKV_EINVAL for null pointers, unsupported dtype, or a page size that is not a multiple
+ * of 16 bytes. */
+int skv_gather_kv(const skv_attn_desc* desc, int32_t n_req, const void* d_kpool, const void* d_vpool,
+                  int32_t n_pages, const int32_t* d_matched_len, const int32_t* d_page_table,
+                  int32_t max_blocks, int64_t* d_ctx_off, void* d_kctx, void* d_vctx,
+                  int64_t ctx_capacity_tokens, void* stream);
+
+/* Bytes of device workspace skv_prefill_attn needs for n_req requests and at most
+ * total_q_rows uncached tokens in the batch. */
+int skv_prefill_attn_workspace_size(const skv_attn_desc* desc, int32_t n_req, int64_t total_q_rows,
+                                    size_t* bytes);
+
+/* Causal GQA prefill attention of the uncached suffixes (Section 2.1).  For request r, suffix
+ * position i in [0, S_r), S_r = d_q_off[r+1] - d_q_off[r], query head h:
+ *   O[q_off[r]+i, h] = softmax_j(scale * q[q_off[r]+i, h] . k_j) . v_j
+ * over j in [0, L_r + i]: first the L_r = d_matched_len[r] reused positions, read from the
+ * pools through d_page_table[r*max_blocks + j/16] at slot j%16, then the request's own new
+ * positions 0..i from d_knew / d_vnew (rows q_off[r] + (j - L_r)).
+ * d_q, d_out: [total rows][n_q_heads][head_dim]; d_knew, d_vnew: [total rows][n_kv_heads][head_dim].
+ * total_q_rows is a host-side upper bound of d_q_off[n_req] (the rows allocated in d_q / d_out);
+ * rows beyond d_q_off[n_req] are left untouched.  S_r == 0 is legal.  Pages with an id outside
+ * [0, n_pages) are read as zeros.  bf16 computes QK^T and PV on the matrix cores with fp32
+ * accumulation and fp32 softmax; fp32 computes in fp32 throughout.
+ * Errors: SKV_EINVAL for null pointers or unsupported shapes, SKV_ENOMEM if the workspace is
+ * smaller than skv_prefill_attn_workspace_size. */
+int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const void* d_q, const void* d_knew,
+                     const void* d_vnew, const int32_t* d_q_off, int64_t total_q_rows,
+                     const void* d_kpool, const void* d_vpool, int32_t n_pages,
+                     const int32_t* d_matched_len, const int32_t* d_page_table, int32_t max_blocks,
+                     void* d_out, void* d_workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKV_H */

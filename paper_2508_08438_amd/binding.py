@@ -1,0 +1,202 @@
+"""Thin ctypes binding of libskv.so: same names as the C ABI, argument marshalling only.
+
+Every step of the path runs in the library's kernels; torch is used for device memory and
+streams.  There is no fallback: if the library is not built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libskv.so")
+BLOCK = 16
+SKV_F32, SKV_BF16 = 0, 1
+
+EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_build",
+           "skv_tree_info", "skv_tree_destroy", "skv_match", "skv_counters_read",
+           "skv_counters_reset", "skv_suffix_offsets", "skv_gather_kv",
+           "skv_prefill_attn_workspace_size", "skv_prefill_attn"]
+
+
+class SkvError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        msg = lib().skv_strerror(code).decode()
+        if code == -4:
+            msg += f" (hipError {lib().skv_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{code}]")
+
+
+class TreeDesc(C.Structure):
+    _fields_ = [("block_tokens", C.c_int32), ("n_tenants", C.c_int32), ("n_pages", C.c_int32),
+                ("n_seq", C.c_int64), ("seq_off", C.c_void_p), ("tokens", C.c_void_p),
+                ("blk_sensitive", C.c_void_p), ("blk_owner", C.c_void_p), ("blk_page", C.c_void_p)]
+
+
+class AttnDesc(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("dtype", C.c_int32), ("scale", C.c_float)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built: run __graft_entry__.build() "
+                               "(there is no fallback path)")
+        l = C.CDLL(LIB_PATH)
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        l.skv_strerror.restype = C.c_char_p
+        l.skv_strerror.argtypes = [C.c_int]
+        l.skv_tree_build_size.argtypes = [C.POINTER(TreeDesc), C.POINTER(C.c_size_t)]
+        l.skv_tree_build.argtypes = [C.POINTER(TreeDesc), vp, C.c_size_t, vp, C.POINTER(vp)]
+        l.skv_tree_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+        l.skv_tree_destroy.argtypes = [vp]
+        l.skv_tree_destroy.restype = None
+        l.skv_match.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, vp]
+        l.skv_counters_read.argtypes = [vp, vp, vp, vp]
+        l.skv_counters_reset.argtypes = [vp, vp]
+        l.skv_suffix_offsets.argtypes = [i32, vp, vp, vp, vp]
+        l.skv_gather_kv.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, i32, vp, vp, i32, vp, vp, vp, i64, vp]
+        l.skv_prefill_attn_workspace_size.argtypes = [C.POINTER(AttnDesc), i32, i64, C.POINTER(C.c_size_t)]
+        l.skv_prefill_attn.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp,
+                                       i32, vp, vp, C.c_size_t, vp]
+        _lib = l
+    return _lib
+
+
+def _check(code, where):
+    if code != 0:
+        raise SkvError(code, where)
+
+
+def _dptr(t):
+    if t is None:
+        return None
+    assert isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous(), "device tensor expected"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def attn_desc(n_q_heads, n_kv_heads, head_dim, dtype, scale=None) -> AttnDesc:
+    code = {torch.float32: SKV_F32, torch.bfloat16: SKV_BF16, "f32": SKV_F32, "bf16": SKV_BF16}[dtype]
+    return AttnDesc(n_q_heads, n_kv_heads, head_dim, code,
+                    float(scale if scale is not None else head_dim ** -0.5))
+
+
+class Tree:
+    """Owner of a tree handle and of the torch tensor that backs its device slab."""
+
+    def __init__(self, handle, slab):
+        self.handle, self.slab = handle, slab
+
+    def info(self):
+        a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+        _check(lib().skv_tree_info(self.handle, C.byref(a), C.byref(b), C.byref(c)), "skv_tree_info")
+        return {"n_nodes": a.value, "n_blocks": b.value, "n_in_blocks": c.value}
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib().skv_tree_destroy(self.handle)
+            self.handle = None
+
+
+def _tree_desc(seq_tokens, seq_off, blk_sensitive, blk_owner, blk_page, n_tenants, n_pages,
+               block_tokens=BLOCK):
+    keep = [np.ascontiguousarray(seq_off, dtype=np.int64), np.ascontiguousarray(seq_tokens, dtype=np.int32),
+            np.ascontiguousarray(blk_sensitive, dtype=np.uint8), np.ascontiguousarray(blk_owner, dtype=np.int32),
+            np.ascontiguousarray(blk_page, dtype=np.int32)]
+    ptr = [C.c_void_p(a.ctypes.data) if a.size or i == 0 else None for i, a in enumerate(keep)]
+    d = TreeDesc(block_tokens, n_tenants, n_pages, len(keep[0]) - 1, *ptr)
+    return d, keep
+
+
+def skv_tree_build_size(seq_tokens, seq_off, blk_sensitive, blk_owner, blk_page, n_tenants, n_pages,
+                        block_tokens=BLOCK) -> int:
+    d, _keep = _tree_desc(seq_tokens, seq_off, blk_sensitive, blk_owner, blk_page, n_tenants, n_pages,
+                          block_tokens)
+    n = C.c_size_t()
+    _check(lib().skv_tree_build_size(C.byref(d), C.byref(n)), "skv_tree_build_size")
+    return n.value
+
+
+def skv_tree_build(seq_tokens, seq_off, blk_sensitive, blk_owner, blk_page, n_tenants, n_pages,
+                   device="cuda", stream=None) -> Tree:
+    d, _keep = _tree_desc(seq_tokens, seq_off, blk_sensitive, blk_owner, blk_page, n_tenants, n_pages)
+    n = C.c_size_t()
+    _check(lib().skv_tree_build_size(C.byref(d), C.byref(n)), "skv_tree_build_size")
+    slab = torch.empty(n.value, dtype=torch.uint8, device=device)
+    h = C.c_void_p()
+    with torch.cuda.device(slab.device):
+        _check(lib().skv_tree_build(C.byref(d), _dptr(slab), n.value, _stream(stream), C.byref(h)),
+               "skv_tree_build")
+    return Tree(h, slab)
+
+
+def skv_match(tree: Tree, req_off, req_tokens, req_tenant, max_blocks, matched_len, page_table, stream=None):
+    n_req = req_tenant.numel()
+    assert req_off.dtype == req_tokens.dtype == req_tenant.dtype == torch.int32
+    assert matched_len.dtype == page_table.dtype == torch.int32
+    assert req_off.numel() == n_req + 1 and matched_len.numel() >= n_req
+    assert page_table.numel() >= n_req * max_blocks
+    _check(lib().skv_match(tree.handle, n_req, _dptr(req_off), _dptr(req_tokens), _dptr(req_tenant),
+                           max_blocks, _dptr(matched_len), _dptr(page_table), _stream(stream)), "skv_match")
+
+
+def skv_counters_read(tree: Tree, hit, ucnt, stream=None):
+    n = tree.info()["n_in_blocks"]
+    assert hit.numel() >= n and ucnt.numel() >= n and hit.dtype == ucnt.dtype == torch.int32
+    _check(lib().skv_counters_read(tree.handle, _dptr(hit), _dptr(ucnt), _stream(stream)), "skv_counters_read")
+
+
+def skv_counters_reset(tree: Tree, stream=None):
+    _check(lib().skv_counters_reset(tree.handle, _stream(stream)), "skv_counters_reset")
+
+
+def skv_suffix_offsets(req_off, matched_len, q_off, stream=None):
+    n_req = matched_len.numel()
+    assert q_off.numel() == n_req + 1 and q_off.dtype == torch.int32
+    _check(lib().skv_suffix_offsets(n_req, _dptr(req_off), _dptr(matched_len), _dptr(q_off), _stream(stream)),
+           "skv_suffix_offsets")
+
+
+def skv_gather_kv(desc: AttnDesc, kpool, vpool, matched_len, page_table, max_blocks, ctx_off, kctx, vctx,
+                  stream=None):
+    n_req = matched_len.numel()
+    assert ctx_off.dtype == torch.int64 and ctx_off.numel() == n_req + 1
+    row = desc.n_kv_heads * desc.head_dim
+    cap = kctx.numel() // row
+    assert vctx.numel() // row >= cap
+    _check(lib().skv_gather_kv(C.byref(desc), n_req, _dptr(kpool), _dptr(vpool), kpool.shape[0],
+                               _dptr(matched_len), _dptr(page_table), max_blocks, _dptr(ctx_off),
+                               _dptr(kctx), _dptr(vctx), cap, _stream(stream)), "skv_gather_kv")
+
+
+def skv_prefill_attn_workspace_size(desc: AttnDesc, n_req, total_q_rows) -> int:
+    n = C.c_size_t()
+    _check(lib().skv_prefill_attn_workspace_size(C.byref(desc), n_req, total_q_rows, C.byref(n)),
+           "skv_prefill_attn_workspace_size")
+    return n.value
+
+
+def skv_prefill_attn(desc: AttnDesc, q, knew, vnew, q_off, kpool, vpool, matched_len, page_table, max_blocks,
+                     out, workspace, stream=None):
+    n_req = matched_len.numel()
+    total = q.shape[0]
+    assert out.shape == q.shape and knew.shape[0] >= total and vnew.shape[0] >= total
+    _check(lib().skv_prefill_attn(C.byref(desc), n_req, _dptr(q), _dptr(knew), _dptr(vnew), _dptr(q_off),
+                                  total, _dptr(kpool), _dptr(vpool), kpool.shape[0], _dptr(matched_len),
+                                  _dptr(page_table), max_blocks, _dptr(out), _dptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream(stream)),
+           "skv_prefill_attn")

@@ -1,0 +1,529 @@
+// Causal GQA prefill attention of the uncached suffix over reused paged prefix KV plus the
+// request's own new KV.
+//
+// SafeKV Section 2.1: inference attends over all previous tokens; with KV caching the K/V of
+// the cached prefix are reused and only the new tokens' part is computed.  Row i of the
+// suffix therefore attends to the L reused positions (read from the page pool through the
+// page table the match produced) and to its own positions 0..i.
+//
+// bf16 path: flash-style streaming over 64-key tiles with online softmax in fp32; the two
+// contractions (K.Q^T and V^T.P^T) run on the matrix cores (v_mfma_f32_32x32x16_bf16), the
+// softmax on the vector ALU.  A workgroup of four wavefronts shares every K/V tile through
+// LDS; each wavefront owns 64 query rows of one head (the query heads of one kv head share a
+// workgroup, so a K/V tile is fetched once for the group).  The products are formed
+// transposed (S^T = K Q^T, O^T = V^T P^T) so that a query is a lane-column of the MFMA
+// accumulator: row max / row sum are register reductions plus one cross-half exchange, and
+// the P^T accumulator registers are already in the B-operand layout of the second product
+// once V^T is stored in LDS with the matching key permutation.
+// fp32 path: one wavefront per output row, plain fp32 arithmetic (correctness configuration).
+#include "skv_internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kD = 128;          // head dim of the bf16 kernel
+constexpr int kBN = 64;          // keys per tile
+constexpr int kRowsPerWave = 64; // query rows per wavefront
+constexpr int kWaves = 4;
+constexpr int kKsStride = kD + 8;    // bf16 elements per K row in LDS (272 B: conflict-free b128 reads)
+constexpr int kVtStride = kBN + 8;   // bf16 elements per V^T row in LDS (144 B)
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct AttnParams {
+  const void *q, *knew, *vnew, *kpool, *vpool;
+  void* out;
+  const int32_t *q_off, *matched_len, *page_table;
+  const int32_t* items;      // int2 {request, q tile}
+  const int32_t* n_items;
+  int n_req, max_blocks, n_pages, Hq, Hkv;
+  int heads_per_wg;          // query heads of one kv head handled by one workgroup (1, 2 or 4)
+  float scale;
+};
+
+// ---- work list ---------------------------------------------------------------------------------
+// One workgroup.  items[] lists (request, q tile) pairs, a request's heaviest (last) tile first.
+__global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_off, int pos_per_wg,
+                                     int max_items, int32_t* __restrict__ n_items, int32_t* __restrict__ items) {
+  __shared__ int32_t sh[1024];
+  __shared__ int32_t carry;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  for (int base = 0; base < n_req; base += 1024) {
+    const int r = base + threadIdx.x;
+    int nt = 0;
+    if (r < n_req) {
+      const int S = q_off[r + 1] - q_off[r];
+      nt = S > 0 ? (S + pos_per_wg - 1) / pos_per_wg : 0;
+    }
+    sh[threadIdx.x] = nt;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      int add = threadIdx.x >= o ? sh[threadIdx.x - o] : 0;
+      __syncthreads();
+      sh[threadIdx.x] += add;
+      __syncthreads();
+    }
+    const int start = carry + sh[threadIdx.x] - nt;
+    for (int k = 0; k < nt; ++k) {
+      if (start + k < max_items) {
+        items[2 * (start + k)] = r;
+        items[2 * (start + k) + 1] = nt - 1 - k;
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) carry += sh[1023];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *n_items = carry < max_items ? carry : max_items;
+}
+
+// ---- bf16 MFMA kernel --------------------------------------------------------------------------
+struct RowSrc {          // where one 16-key group of a tile lives
+  const __bf16* k;       // first row of the group for this kv head (nullptr: no data)
+  const __bf16* v;
+  int n_valid;           // rows of the group that exist (0..16)
+};
+
+__device__ inline RowSrc group_source(const AttnParams& p, int r, int kvh, int L, int Ltot, int qbase, int key0) {
+  RowSrc s{nullptr, nullptr, 0};
+  if (key0 >= Ltot) return s;
+  if (key0 < L) {
+    const int page = p.page_table[(size_t)r * p.max_blocks + key0 / SKV_BLOCK_TOKENS];
+    if (page < 0 || page >= p.n_pages) return s;
+    const size_t off = ((size_t)page * SKV_BLOCK_TOKENS * p.Hkv + kvh) * kD;
+    s.k = (const __bf16*)p.kpool + off;
+    s.v = (const __bf16*)p.vpool + off;
+    s.n_valid = 16;
+  } else {
+    const size_t off = ((size_t)(qbase + key0 - L) * p.Hkv + kvh) * kD;
+    s.k = (const __bf16*)p.knew + off;
+    s.v = (const __bf16*)p.vnew + off;
+    s.n_valid = min(16, Ltot - key0);
+  }
+  return s;
+}
+
+__device__ inline uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
+__device__ inline uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+
+__global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnParams p) {
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[kBN * kKsStride];
+  __shared__ __attribute__((aligned(16))) __bf16 Vt[kD * kVtStride];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int l32 = lane & 31;
+  const int half = lane >> 5;
+
+  // ---- which piece of work: XCD-aware decode (workgroup b runs on XCD b % 8) ----
+  const int G = p.Hq / p.Hkv;
+  const int n_hg = G / p.heads_per_wg;               // head groups per kv head
+  const int pos_tiles = kWaves / p.heads_per_wg;     // 64-row position tiles per workgroup
+  const int pos_per_wg = pos_tiles * kRowsPerWave;
+  int item, kvh, hg;
+  {
+    const int b = blockIdx.x;
+    if (p.Hkv % 8 == 0) {
+      // all work of one kv head stays on one XCD, so its K/V tiles are re-read from that XCD's L2
+      const int per = p.Hkv / 8;
+      const int xcd = b & 7, slot = b >> 3;
+      kvh = xcd + 8 * (slot % per);
+      const int rest = slot / per;
+      hg = rest % n_hg;
+      item = rest / n_hg;
+    } else {
+      kvh = b % p.Hkv;
+      const int rest = b / p.Hkv;
+      hg = rest % n_hg;
+      item = rest / n_hg;
+    }
+  }
+  if (item >= *p.n_items) return;
+  const int r = p.items[2 * item];
+  const int qt = p.items[2 * item + 1];
+  const int qbase = p.q_off[r];
+  const int S = p.q_off[r + 1] - qbase;
+  const int L = p.matched_len[r] > 0 ? p.matched_len[r] : 0;
+  const int Ltot = L + S;
+
+  const int head = kvh * G + hg * p.heads_per_wg + (wave % p.heads_per_wg);
+  const int pos0 = qt * pos_per_wg + (wave / p.heads_per_wg) * kRowsPerWave;  // first row of this wave
+  const bool wave_active = pos0 < S;
+  const int wg_pos_end = min(S, (qt + 1) * pos_per_wg);
+  const int n_tiles = (L + wg_pos_end + kBN - 1) / kBN;
+  const int wave_key_end = L + min(S, pos0 + kRowsPerWave);  // keys this wave needs: [0, wave_key_end)
+
+  // ---- Q fragments (B operand of S^T = K Q^T): lane holds query l32 (+32 nt), d = 16 ks + 8 half .. +7
+  bf16x8 qf[2][8];
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    int row = pos0 + nt * 32 + l32;
+    row = min(row, S - 1);
+    row = max(row, 0);
+    const __bf16* src = (const __bf16*)p.q + ((size_t)(qbase + row) * p.Hq + head) * kD + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[nt][ks] = *(const bf16x8*)(src + ks * 16);
+  }
+
+  f32x16 o[4][2];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[a][b][i] = 0.f;
+  float m_run[2] = {-INFINITY, -INFINITY};
+  float l_run[2] = {0.f, 0.f};
+  const float c = p.scale * kLog2e;
+
+  // staging registers for the next tile
+  u32x4 kreg[4];
+  u32x2 vreg[2][4];
+  const size_t row_stride = (size_t)p.Hkv * kD;
+
+  auto load_tile = [&](int kt) {
+    const int key_base = kt * kBN;
+    // K: chunk cc covers keys 16cc..16cc+15; 16 threads x 16 B per key row
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+      const RowSrc g = group_source(p, r, kvh, L, Ltot, qbase, key_base + cc * 16);
+      const int row = tid >> 4, part = tid & 15;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (row < g.n_valid) v = *(const u32x4*)(g.k + (size_t)row * row_stride + part * 8);
+      kreg[cc] = v;
+    }
+    // V: task = 4 consecutive keys x 4 consecutive d; tasks tid and tid + 256
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2) {
+      const int task = tid + 256 * c2;
+      const int dq = task & 31, kq = task >> 5;  // kq in 0..15: keys 4kq..4kq+3
+      const RowSrc g = group_source(p, r, kvh, L, Ltot, qbase, key_base + (kq >> 2) * 16);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int row = (kq & 3) * 4 + e;
+        u32x2 v = {0u, 0u};
+        if (row < g.n_valid) v = *(const u32x2*)(g.v + (size_t)row * row_stride + dq * 4);
+        vreg[c2][e] = v;
+      }
+    }
+  };
+
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+      const int row = cc * 16 + (tid >> 4), part = tid & 15;
+      *(u32x4*)(Ks + row * kKsStride + part * 8) = kreg[cc];
+    }
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2) {
+      const int task = tid + 256 * c2;
+      const int dq = task & 31, kq = task >> 5;
+      // LDS key position: inside each 16-key group the order is {0-3, 8-11, 4-7, 12-15}, which is
+      // the order in which the P^T accumulator registers of one lane-half enumerate the keys
+      const int o4 = kq & 3;
+      const int pos = (kq >> 2) * 16 + (o4 & 1) * 8 + (o4 >> 1) * 4;
+      const u32x2 k0 = vreg[c2][0], k1 = vreg[c2][1], k2 = vreg[c2][2], k3 = vreg[c2][3];
+      u32x2 r0 = {pack_lo(k0.x, k1.x), pack_lo(k2.x, k3.x)};
+      u32x2 r1 = {pack_hi(k0.x, k1.x), pack_hi(k2.x, k3.x)};
+      u32x2 r2 = {pack_lo(k0.y, k1.y), pack_lo(k2.y, k3.y)};
+      u32x2 r3 = {pack_hi(k0.y, k1.y), pack_hi(k2.y, k3.y)};
+      __bf16* dst = Vt + (dq * 4) * kVtStride + pos;
+      *(u32x2*)(dst) = r0;
+      *(u32x2*)(dst + kVtStride) = r1;
+      *(u32x2*)(dst + 2 * kVtStride) = r2;
+      *(u32x2*)(dst + 3 * kVtStride) = r3;
+    }
+  };
+
+  load_tile(0);
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    store_tile();
+    __syncthreads();
+    if (kt + 1 < n_tiles) load_tile(kt + 1);  // in flight during the math below
+
+    const int key_base = kt * kBN;
+    if (wave_active && key_base < wave_key_end) {
+      // ---- S^T = K Q^T : [64 keys][64 queries] as 2x2 tiles of 32x32
+      f32x16 s[2][2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[a][b][i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+          const bf16x8 a = *(const bf16x8*)(Ks + (mt * 32 + l32) * kKsStride + ks * 16 + 8 * half);
+          s[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][ks], s[mt][0], 0, 0, 0);
+          s[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][ks], s[mt][1], 0, 0, 0);
+        }
+      }
+      // ---- causal mask on tiles that reach past the first row's limit
+      if (key_base + kBN - 1 > L + pos0) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+          const int limit = L + pos0 + nt * 32 + l32;  // last visible key of this lane's query
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int key = key_base + mt * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
+              if (key > limit) s[mt][nt][i] = -INFINITY;
+            }
+        }
+      }
+      // ---- online softmax (per query = per lane column), P^T packed to bf16 B operands
+      bf16x8 pb[2][4];
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        float mx = s[0][nt][0];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[mt][nt][i]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[nt], mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_run[nt] - m_new) * c);
+        const float mc = m_new * c;
+        float sum = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float e = __builtin_amdgcn_exp2f(s[mt][nt][i] * c - mc);
+            s[mt][nt][i] = e;
+            sum += e;
+          }
+        l_run[nt] = l_run[nt] * alpha + sum;
+        m_run[nt] = m_new;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[a][nt][i] *= alpha;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int q2 = 0; q2 < 2; ++q2) {
+            bf16x8 pk;
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+              f32x2 pr = {s[mt][nt][q2 * 8 + e], s[mt][nt][q2 * 8 + e + 1]};
+              bf16x2 cv = __builtin_convertvector(pr, bf16x2);
+              pk[e] = cv[0];
+              pk[e + 1] = cv[1];
+            }
+            pb[nt][mt * 2 + q2] = pk;
+          }
+      }
+      // ---- O^T += V^T P^T : [128 d][64 queries]; k-step g16 covers keys 16 g16 .. +15 of the tile
+#pragma unroll
+      for (int g16 = 0; g16 < 4; ++g16) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          const bf16x8 va = *(const bf16x8*)(Vt + (a * 32 + l32) * kVtStride + g16 * 16 + 8 * half);
+          o[a][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[0][g16], o[a][0], 0, 0, 0);
+          o[a][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[1][g16], o[a][1], 0, 0, 0);
+        }
+      }
+    }
+    __syncthreads();  // everyone is done with this tile before it is overwritten
+  }
+
+  // ---- normalise and store: lane holds query l32 (+32 nt); d = 32 a + 8 (i/4) + 4 half + i%4
+  if (!wave_active) return;
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    const float lsum = l_run[nt] + __shfl_xor(l_run[nt], 32);
+    const float inv = 1.0f / lsum;
+    const int pos = pos0 + nt * 32 + l32;
+    if (pos < S) {
+      __bf16* dst = (__bf16*)p.out + ((size_t)(qbase + pos) * p.Hq + head) * kD + 4 * half;
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          f32x2 x0 = {o[a][nt][i4 * 4 + 0] * inv, o[a][nt][i4 * 4 + 1] * inv};
+          f32x2 x1 = {o[a][nt][i4 * 4 + 2] * inv, o[a][nt][i4 * 4 + 3] * inv};
+          bf16x2 y0 = __builtin_convertvector(x0, bf16x2);
+          bf16x2 y1 = __builtin_convertvector(x1, bf16x2);
+          u32x2 w = {__builtin_bit_cast(uint32_t, y0), __builtin_bit_cast(uint32_t, y1)};
+          *(u32x2*)(dst + a * 32 + i4 * 8) = w;
+        }
+    }
+  }
+}
+
+// ---- fp32 kernel: one wavefront per (token, head) output row ----------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p, int64_t max_rows) {
+  __shared__ float red[64 * (D + 1)];
+  const int lane = threadIdx.x;
+  const int64_t g = blockIdx.x;  // token row * Hq + head
+  const int h = (int)(g % p.Hq);
+  const int64_t tok = g / p.Hq;
+  if (tok >= max_rows || tok >= p.q_off[p.n_req]) return;
+  int lo = 0, hi = p.n_req;  // q_off[lo] <= tok < q_off[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (p.q_off[mid] <= tok) lo = mid; else hi = mid;
+  }
+  const int r = lo;
+  const int qbase = p.q_off[r];
+  const int i = (int)(tok - qbase);
+  const int L = p.matched_len[r] > 0 ? p.matched_len[r] : 0;
+  const int n_keys = L + i + 1;
+  const int hk = h / (p.Hq / p.Hkv);
+  const float* q = (const float*)p.q + ((size_t)tok * p.Hq + h) * D;
+  float qv[D];
+#pragma unroll
+  for (int c = 0; c < D; ++c) qv[c] = q[c];
+  float m = -INFINITY, l = 0.f;
+  float acc[D];
+#pragma unroll
+  for (int c = 0; c < D; ++c) acc[c] = 0.f;
+  for (int j = lane; j < n_keys; j += 64) {
+    const float *kr = nullptr, *vr = nullptr;
+    if (j < L) {
+      const int page = p.page_table[(size_t)r * p.max_blocks + j / SKV_BLOCK_TOKENS];
+      if (page >= 0 && page < p.n_pages) {
+        const size_t off = (((size_t)page * SKV_BLOCK_TOKENS + j % SKV_BLOCK_TOKENS) * p.Hkv + hk) * D;
+        kr = (const float*)p.kpool + off;
+        vr = (const float*)p.vpool + off;
+      }
+    } else {
+      const size_t off = ((size_t)(qbase + j - L) * p.Hkv + hk) * D;
+      kr = (const float*)p.knew + off;
+      vr = (const float*)p.vnew + off;
+    }
+    float s = 0.f;
+    if (kr) {
+#pragma unroll
+      for (int c = 0; c < D; c += 4) {
+        const float4 kk = *(const float4*)(kr + c);
+        s += qv[c] * kk.x + qv[c + 1] * kk.y + qv[c + 2] * kk.z + qv[c + 3] * kk.w;
+      }
+    }
+    s *= p.scale;
+    const float m_new = fmaxf(m, s);
+    const float alpha = expf(m - m_new);
+    const float e = expf(s - m_new);
+    l = l * alpha + e;
+#pragma unroll
+    for (int c = 0; c < D; c += 4) {
+      float4 vv = {0.f, 0.f, 0.f, 0.f};
+      if (vr) vv = *(const float4*)(vr + c);
+      acc[c] = acc[c] * alpha + e * vv.x;
+      acc[c + 1] = acc[c + 1] * alpha + e * vv.y;
+      acc[c + 2] = acc[c + 2] * alpha + e * vv.z;
+      acc[c + 3] = acc[c + 3] * alpha + e * vv.w;
+    }
+    m = m_new;
+  }
+  // merge the 64 partial softmaxes
+  float mw = m;
+  for (int o = 32; o >= 1; o >>= 1) mw = fmaxf(mw, __shfl_xor(mw, o));
+  const float f = m == -INFINITY ? 0.f : expf(m - mw);
+  float lw = l * f;
+  for (int o = 32; o >= 1; o >>= 1) lw += __shfl_xor(lw, o);
+#pragma unroll
+  for (int c = 0; c < D; ++c) red[lane * (D + 1) + c] = acc[c] * f;
+  __syncthreads();
+  float* out = (float*)p.out + ((size_t)tok * p.Hq + h) * D;
+  for (int c = lane; c < D; c += 64) {
+    float sum = 0.f;
+    for (int t = 0; t < 64; ++t) sum += red[t * (D + 1) + c];
+    out[c] = sum / lw;
+  }
+}
+
+int heads_per_wg_for(int G) { return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1); }
+
+int check_attn(const skv_attn_desc* d) {
+  if (!d) return SKV_EINVAL;
+  if (d->n_q_heads < 1 || d->n_kv_heads < 1 || d->n_q_heads % d->n_kv_heads) return SKV_EINVAL;
+  if (d->dtype == SKV_BF16) return d->head_dim == kD ? SKV_OK : SKV_EINVAL;
+  if (d->dtype == SKV_F32) return (d->head_dim == 64 || d->head_dim == 128) ? SKV_OK : SKV_EINVAL;
+  return SKV_EINVAL;
+}
+
+int64_t max_items_for(const skv_attn_desc* d, int32_t n_req, int64_t total_q_rows) {
+  if (d->dtype != SKV_BF16) return 0;
+  const int hpw = heads_per_wg_for(d->n_q_heads / d->n_kv_heads);
+  const int pos_per_wg = (kWaves / hpw) * kRowsPerWave;
+  return total_q_rows / pos_per_wg + n_req;
+}
+
+}  // namespace
+
+extern "C" int skv_prefill_attn_workspace_size(const skv_attn_desc* desc, int32_t n_req,
+                                               int64_t total_q_rows, size_t* bytes) {
+  int rc = check_attn(desc);
+  if (rc) return rc;
+  if (n_req < 0 || total_q_rows < 0 || !bytes) return SKV_EINVAL;
+  *bytes = 256 + skv_align256((size_t)max_items_for(desc, n_req, total_q_rows) * 2 * sizeof(int32_t));
+  return SKV_OK;
+}
+
+extern "C" int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const void* d_q,
+                                const void* d_knew, const void* d_vnew, const int32_t* d_q_off,
+                                int64_t total_q_rows, const void* d_kpool, const void* d_vpool,
+                                int32_t n_pages, const int32_t* d_matched_len,
+                                const int32_t* d_page_table, int32_t max_blocks, void* d_out,
+                                void* d_workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_attn(desc);
+  if (rc) return rc;
+  if (n_req < 0 || total_q_rows < 0 || n_pages < 0 || max_blocks < 0) return SKV_EINVAL;
+  if (n_req == 0 || total_q_rows == 0) return SKV_OK;
+  if (!d_q || !d_knew || !d_vnew || !d_q_off || !d_matched_len || !d_out) return SKV_EINVAL;
+  if (max_blocks > 0 && (!d_page_table || !d_kpool || !d_vpool)) return SKV_EINVAL;
+  if (((uintptr_t)d_q | (uintptr_t)d_knew | (uintptr_t)d_vnew | (uintptr_t)d_kpool | (uintptr_t)d_vpool |
+       (uintptr_t)d_out) & 15)
+    return SKV_EINVAL;
+  size_t need = 0;
+  skv_prefill_attn_workspace_size(desc, n_req, total_q_rows, &need);
+  if (!d_workspace || workspace_bytes < need) return SKV_ENOMEM;
+  if ((uintptr_t)d_workspace & 15) return SKV_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+
+  AttnParams p;
+  p.q = d_q; p.knew = d_knew; p.vnew = d_vnew; p.kpool = d_kpool; p.vpool = d_vpool; p.out = d_out;
+  p.q_off = d_q_off; p.matched_len = d_matched_len; p.page_table = d_page_table;
+  p.n_items = (const int32_t*)d_workspace;
+  p.items = (const int32_t*)((char*)d_workspace + 256);
+  p.n_req = n_req; p.max_blocks = max_blocks; p.n_pages = n_pages;
+  p.Hq = desc->n_q_heads; p.Hkv = desc->n_kv_heads;
+  p.heads_per_wg = heads_per_wg_for(desc->n_q_heads / desc->n_kv_heads);
+  p.scale = desc->scale;
+
+  if (desc->dtype == SKV_F32) {
+    const int64_t rows = total_q_rows * desc->n_q_heads;
+    if (rows > 0x7fffffff) return SKV_ERANGE;
+    if (desc->head_dim == 64)
+      attn_f32_kernel<64><<<(int)rows, 64, 0, st>>>(p, total_q_rows);
+    else
+      attn_f32_kernel<128><<<(int)rows, 64, 0, st>>>(p, total_q_rows);
+    SKV_HIP(hipGetLastError());
+    return SKV_OK;
+  }
+
+  const int64_t max_items = max_items_for(desc, n_req, total_q_rows);
+  const int pos_per_wg = (kWaves / p.heads_per_wg) * kRowsPerWave;
+  const int n_hg = (desc->n_q_heads / desc->n_kv_heads) / p.heads_per_wg;
+  const int64_t grid = max_items * desc->n_kv_heads * n_hg;
+  if (grid > 0x7fffffff || max_items > 0x3fffffff) return SKV_ERANGE;
+  attn_schedule_kernel<<<1, 1024, 0, st>>>(n_req, d_q_off, pos_per_wg, (int)max_items,
+                                           (int32_t*)d_workspace, (int32_t*)((char*)d_workspace + 256));
+  SKV_HIP(hipGetLastError());
+  attn_bf16_kernel<<<(int)grid, 256, 0, st>>>(p);
+  SKV_HIP(hipGetLastError());
+  return SKV_OK;
+}

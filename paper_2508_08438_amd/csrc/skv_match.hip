@@ -1,0 +1,194 @@
+// Longest visible prefix match + access-monitor update, one wavefront per request.
+//
+// SafeKV Section 4.3.1 (Search): the lookup walks the prefix path and checks private_tag at
+// every hop; a private entry may only be used by its creator_id, otherwise the walk stops.
+// Section 4.3.2: at a compressed node the walk reads the KV addresses from the node's address
+// vector instead of chasing one pointer per block.  Section 4.2.2: every lookup records per
+// KV block the hit count and the distinct tenants of the current window.
+//
+// Mapping to the wavefront: lane i compares request token i with tree token i of a window of
+// the node's contiguous token span; a ballot of the mismatches gives the first block that
+// differs, a second ballot over the blocks' metadata gives the first block the tenant may
+// not see; the smaller of the two ends the walk.  The lanes of the matched blocks then copy
+// the page ids and issue the counter atomics.
+#include "skv_internal.h"
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kWavesPerWg = 4;
+constexpr int kSub = 8;                    // 64-token sub-windows per step
+constexpr int kStepBlocks = kSub * 4;      // 32 blocks (512 tokens) per step
+
+__device__ inline uint64_t ballot64(bool p) { return __ballot(p); }
+
+__device__ inline int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// 64-bit hash of the 16-token block starting at x (all lanes return the same value)
+__device__ inline uint64_t hash_block(const int32_t* x, int lane) {
+  uint64_t v = 0;
+  if (lane < 16) v = skv_mix_tok((uint32_t)x[lane], (uint32_t)lane);
+  for (int o = 8; o >= 1; o >>= 1) {
+    uint32_t lo = __shfl_xor((uint32_t)v, o, 16);
+    uint32_t hi = __shfl_xor((uint32_t)(v >> 32), o, 16);
+    v += ((uint64_t)hi << 32) | lo;
+  }
+  v = skv_hash_fin(v);
+  uint32_t lo = (uint32_t)uniform((int)(uint32_t)v);
+  uint32_t hi = (uint32_t)uniform((int)(uint32_t)(v >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// true iff the 16 tokens at a and b are equal (wave-uniform result)
+__device__ inline bool block_equal(const int32_t* a, const int32_t* b, int lane) {
+  bool ne = lane < 16 && a[lane] != b[lane];
+  return ballot64(ne) == 0;
+}
+
+// child of `nd` whose first block equals the request block at x, or -1
+__device__ inline int find_child(const SkvTreeDev& t, const SkvNode nd, const int32_t* x, int lane) {
+  if (nd.tab_cap == 0) return -1;
+  const uint64_t h = hash_block(x, lane);
+  const uint32_t mask = (uint32_t)nd.tab_cap - 1u;
+  for (int base = 0; base < nd.tab_cap; base += kWave) {
+    const bool valid = base + lane < nd.tab_cap;
+    SkvSlot e{0, 0, -1, 0};
+    if (valid) e = t.slots[nd.tab_off + (((uint32_t)h + (uint32_t)(base + lane)) & mask)];
+    const uint64_t empty = ballot64(valid && e.child < 0);
+    uint64_t cand = ballot64(valid && e.child >= 0 && e.hash_lo == (uint32_t)h && e.hash_hi == (uint32_t)(h >> 32));
+    if (empty) cand &= (empty & (~empty + 1)) - 1;  // only slots probed before the first empty one
+    while (cand) {
+      const int l = __builtin_ctzll(cand);
+      const int child = __shfl(e.child, l);
+      const int cfirst = uniform(t.nodes[child].first);
+      if (block_equal(x, t.tok + (size_t)cfirst * 16, lane)) return child;
+      cand &= cand - 1;  // same hash, different tokens: keep probing
+    }
+    if (empty) return -1;
+  }
+  return -1;
+}
+
+__global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
+    SkvTreeDev t, int n_req, const int32_t* __restrict__ req_off, const int32_t* __restrict__ req_tok,
+    const int32_t* __restrict__ req_tenant, int max_blocks, int32_t* __restrict__ matched_len,
+    int32_t* __restrict__ page_table) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int r = blockIdx.x * kWavesPerWg + (threadIdx.x >> 6);
+  if (r >= n_req) return;  // whole wave leaves; the kernel has no barriers
+  const int lo = uniform(req_off[r]), hi = uniform(req_off[r + 1]);
+  const int tenant = uniform(req_tenant[r]);
+  int nb = hi > lo ? (hi - lo) / SKV_BLOCK_TOKENS : 0;
+  if (nb > max_blocks) nb = max_blocks;
+  if (tenant < 0 || tenant >= t.n_tenants) nb = 0;
+  const int32_t* x = req_tok + lo;
+  int32_t* row = page_table + (size_t)r * max_blocks;
+  const uint32_t tbit = 1u << (tenant & 31);
+  const int tword = 1 + (tenant >> 5);
+
+  int j = 0;      // blocks matched so far
+  int node = 0;   // current node (root)
+  bool stop = false;
+  while (j < nb && !stop) {
+    SkvNode cur = t.nodes[node];
+    cur.tab_off = uniform(cur.tab_off);
+    cur.tab_cap = uniform(cur.tab_cap);
+    const int child = find_child(t, cur, x + (size_t)j * 16, lane);
+    if (child < 0) break;
+    SkvNode nd = t.nodes[child];
+    const int first = uniform(nd.first);
+    const int nblk = uniform(nd.n_blocks);
+    const int span = min(nblk, nb - j);  // blocks of this node the request can still cover
+    for (int c = 0; c < span && !stop; c += kStepBlocks) {
+      const int cb = min(kStepBlocks, span - c);
+      const int ntok = cb * 16;
+      const int32_t* tt = t.tok + (size_t)(first + c) * 16;
+      const int32_t* xx = x + (size_t)j * 16;
+      int32_t a[kSub], b[kSub];
+#pragma unroll
+      for (int u = 0; u < kSub; ++u) {
+        const int i = u * kWave + lane;
+        a[u] = i < ntok ? xx[i] : 0;
+        b[u] = i < ntok ? tt[i] : 0;
+      }
+      const int m = lane < cb ? t.meta[first + c + lane] : 0;
+      int n_eq = cb;  // leading blocks whose tokens all agree
+#pragma unroll
+      for (int u = kSub - 1; u >= 0; --u) {
+        const uint64_t ne = ballot64(a[u] != b[u]);
+        if (ne) n_eq = u * 4 + (__builtin_ctzll(ne) >> 4);
+      }
+      // visibility rule: private (bit 31) entries only for their creator
+      const uint64_t hidden = ballot64(m < 0 && (m & 0x7fffffff) != tenant);
+      const int n_vis = hidden ? __builtin_ctzll(hidden) : cb;
+      const int take = min(n_eq, n_vis);
+      if (lane < take) {
+        const int blk = first + c + lane;
+        row[j + lane] = t.page[blk];
+        uint32_t* ctr = t.ctr + (size_t)blk * SKV_CTR_STRIDE;
+        atomicAdd(ctr, 1u);
+        atomicOr(ctr + tword, tbit);
+      }
+      j += take;
+      if (take < cb) stop = true;
+    }
+    node = child;
+  }
+  if (lane == 0) matched_len[r] = j * SKV_BLOCK_TOKENS;
+  for (int i = j + lane; i < max_blocks; i += kWave) row[i] = -1;
+}
+
+__global__ void skv_suffix_offsets_kernel(int n_req, const int32_t* __restrict__ req_off,
+                                          const int32_t* __restrict__ matched_len,
+                                          int32_t* __restrict__ q_off) {
+  // one workgroup; chunked inclusive scan with a running carry
+  __shared__ int32_t sh[1024];
+  __shared__ int32_t carry;
+  if (threadIdx.x == 0) { carry = 0; q_off[0] = 0; }
+  __syncthreads();
+  for (int base = 0; base < n_req; base += 1024) {
+    const int r = base + threadIdx.x;
+    int v = 0;
+    if (r < n_req) {
+      v = req_off[r + 1] - req_off[r] - matched_len[r];
+      if (v < 0) v = 0;
+    }
+    sh[threadIdx.x] = v;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      int add = threadIdx.x >= o ? sh[threadIdx.x - o] : 0;
+      __syncthreads();
+      sh[threadIdx.x] += add;
+      __syncthreads();
+    }
+    if (r < n_req) q_off[r + 1] = carry + sh[threadIdx.x];
+    __syncthreads();
+    if (threadIdx.x == 0) carry += sh[1023];
+    __syncthreads();
+  }
+}
+
+}  // namespace
+
+extern "C" int skv_match(skv_tree* t, int32_t n_req, const int32_t* d_req_off,
+                         const int32_t* d_req_tokens, const int32_t* d_req_tenant, int32_t max_blocks,
+                         int32_t* d_matched_len, int32_t* d_page_table, void* stream) {
+  if (!t || n_req < 0 || max_blocks < 0) return SKV_EINVAL;
+  if (n_req == 0) return SKV_OK;
+  if (!d_req_off || !d_req_tokens || !d_req_tenant || !d_matched_len) return SKV_EINVAL;
+  if (max_blocks > 0 && !d_page_table) return SKV_EINVAL;
+  const int grid = (n_req + kWavesPerWg - 1) / kWavesPerWg;
+  skv_match_kernel<<<grid, kWave * kWavesPerWg, 0, (hipStream_t)stream>>>(
+      t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table);
+  SKV_HIP(hipGetLastError());
+  return SKV_OK;
+}
+
+extern "C" int skv_suffix_offsets(int32_t n_req, const int32_t* d_req_off, const int32_t* d_matched_len,
+                                  int32_t* d_q_off, void* stream) {
+  if (n_req < 0 || !d_q_off) return SKV_EINVAL;
+  if (n_req > 0 && (!d_req_off || !d_matched_len)) return SKV_EINVAL;
+  skv_suffix_offsets_kernel<<<1, 1024, 0, (hipStream_t)stream>>>(n_req, d_req_off, d_matched_len, d_q_off);
+  SKV_HIP(hipGetLastError());
+  return SKV_OK;
+}

@@ -1,0 +1,282 @@
+// Index construction (host) and counter read-back / reset kernels.
+//
+// SafeKV Section 4.3.1 (Insert: blocks are appended along the radix-tree path, each entry
+// recording private_tag and creator_id) and Section 4.3.2 (path compression: a chain is
+// collapsed into one composite node that aggregates the KV addresses of the chain in a
+// vector).  The tree is built without pointers: every distinct block-prefix gets an id
+// through one hash table keyed by (parent id, 16 tokens); non-branching runs are then laid
+// out contiguously and only branch points keep a child table.
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "skv_internal.h"
+
+static thread_local int g_last_hip_error = 0;
+void skv_set_hip_error(int e) { g_last_hip_error = e; }
+
+extern "C" int skv_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" const char* skv_strerror(int code) {
+  switch (code) {
+    case SKV_OK: return "ok";
+    case SKV_EINVAL: return "invalid argument";
+    case SKV_ENOMEM: return "caller-provided device buffer too small";
+    case SKV_ERANGE: return "value exceeds a built-in limit";
+    case SKV_EHIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+namespace {
+
+struct Layout {  // byte offsets inside the slab
+  size_t tok, page, meta, canon, ctr, nodes, slots, total;
+};
+
+Layout make_layout(size_t n_blocks, size_t n_nodes_incl_root, size_t n_slots) {
+  Layout l;
+  size_t o = 0;
+  l.tok = o;   o = skv_align256(o + n_blocks * 16 * sizeof(int32_t));
+  l.page = o;  o = skv_align256(o + n_blocks * sizeof(int32_t));
+  l.meta = o;  o = skv_align256(o + n_blocks * sizeof(int32_t));
+  l.canon = o; o = skv_align256(o + n_blocks * sizeof(int32_t));
+  l.nodes = o; o = skv_align256(o + n_nodes_incl_root * sizeof(SkvNode));
+  l.slots = o; o = skv_align256(o + (n_slots ? n_slots : 1) * sizeof(SkvSlot));
+  l.ctr = o;   o = skv_align256(o + n_blocks * SKV_CTR_STRIDE * sizeof(uint32_t));
+  l.total = o;
+  return l;
+}
+
+int check_desc(const skv_tree_desc* d, int64_t* n_in_blocks) {
+  if (!d || !d->seq_off) return SKV_EINVAL;
+  if (d->block_tokens != SKV_BLOCK_TOKENS) return SKV_EINVAL;
+  if (d->n_tenants < 1 || d->n_tenants > SKV_MAX_TENANTS) return SKV_ERANGE;
+  if (d->n_pages < 1 || d->n_seq < 0) return SKV_EINVAL;
+  if (d->seq_off[0] != 0) return SKV_EINVAL;
+  for (int64_t s = 0; s < d->n_seq; ++s) {
+    if (d->seq_off[s + 1] < d->seq_off[s] || d->seq_off[s + 1] % SKV_BLOCK_TOKENS) return SKV_EINVAL;
+  }
+  int64_t nib = d->seq_off[d->n_seq] / SKV_BLOCK_TOKENS;
+  if (nib > 0x7fffffff / 32) return SKV_ERANGE;
+  if (nib > 0 && (!d->tokens || !d->blk_sensitive || !d->blk_owner || !d->blk_page)) return SKV_EINVAL;
+  *n_in_blocks = nib;
+  return SKV_OK;
+}
+
+uint32_t next_pow2(uint32_t x) {
+  uint32_t p = 1;
+  while (p < x) p <<= 1;
+  return p;
+}
+
+__global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = v;
+}
+
+__global__ void counters_scatter_kernel(SkvTreeDev t, uint32_t* hit, uint32_t* ucnt) {
+  for (int b = blockIdx.x * blockDim.x + threadIdx.x; b < t.n_blocks; b += gridDim.x * blockDim.x) {
+    const uint32_t* c = t.ctr + (size_t)b * SKV_CTR_STRIDE;
+    int id = t.canon[b];
+    hit[id] = c[0];
+    ucnt[id] = __popc(c[1]) + __popc(c[2]) + __popc(c[3]) + __popc(c[4]);
+  }
+}
+
+int grid_for(size_t n, int block) {
+  size_t g = (n + block - 1) / block;
+  if (g < 1) g = 1;
+  if (g > 4096) g = 4096;
+  return (int)g;
+}
+
+}  // namespace
+
+extern "C" int skv_tree_build_size(const skv_tree_desc* desc, size_t* device_bytes) {
+  int64_t nib = 0;
+  int rc = check_desc(desc, &nib);
+  if (rc) return rc;
+  if (!device_bytes) return SKV_EINVAL;
+  *device_bytes = make_layout((size_t)nib, (size_t)nib + 1, 4 * (size_t)nib + 4).total;
+  return SKV_OK;
+}
+
+extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes, void* stream,
+                              skv_tree** out) {
+  int64_t nib64 = 0;
+  int rc = check_desc(d, &nib64);
+  if (rc) return rc;
+  if (!out || !d_slab || ((uintptr_t)d_slab & 255)) return SKV_EINVAL;
+  const int32_t nib = (int32_t)nib64;
+  for (int32_t b = 0; b < nib; ++b) {
+    if (d->blk_owner[b] < 0 || d->blk_owner[b] >= d->n_tenants) return SKV_EINVAL;
+    if (d->blk_page[b] < 0 || d->blk_page[b] >= d->n_pages) return SKV_EINVAL;
+  }
+
+  // 1. one id per distinct block-prefix: hash table over (parent id, 16 tokens), first wins
+  std::vector<int32_t> parent, src, n_child, only_child;
+  std::vector<uint64_t> bhash;  // hash of the block's own 16 tokens
+  parent.reserve(nib); src.reserve(nib); n_child.reserve(nib); only_child.reserve(nib); bhash.reserve(nib);
+  const uint32_t cap = next_pow2((uint32_t)(2 * (size_t)nib + 2));
+  std::vector<int32_t> table(cap, -1);
+  int32_t root_children = 0;
+  for (int64_t s = 0; s < d->n_seq; ++s) {
+    int32_t par = -1;
+    for (int64_t b = d->seq_off[s] / 16; b < d->seq_off[s + 1] / 16; ++b) {
+      const int32_t* tk = d->tokens + b * 16;
+      const uint64_t hb = skv_hash_block_host(tk);
+      uint32_t slot = (uint32_t)skv_hash_fin(hb + 0x632BE59BD9B4E019ull * (uint64_t)(uint32_t)(par + 1)) & (cap - 1);
+      int32_t id;
+      for (;;) {
+        id = table[slot];
+        if (id < 0) break;
+        if (parent[id] == par && bhash[id] == hb && !memcmp(d->tokens + (size_t)src[id] * 16, tk, 64)) break;
+        slot = (slot + 1) & (cap - 1);
+      }
+      if (id < 0) {
+        id = (int32_t)parent.size();
+        table[slot] = id;
+        parent.push_back(par); src.push_back((int32_t)b); n_child.push_back(0);
+        only_child.push_back(-1); bhash.push_back(hb);
+        if (par < 0) ++root_children; else { n_child[par]++; only_child[par] = id; }
+      }
+      par = id;
+    }
+  }
+  const int32_t n_blocks = (int32_t)parent.size();
+  {  // one KV page may back only one cached block
+    std::vector<uint8_t> used((size_t)d->n_pages, 0);
+    for (int32_t b = 0; b < n_blocks; ++b) {
+      int32_t p = d->blk_page[src[b]];
+      if (used[p]) return SKV_EINVAL;
+      used[p] = 1;
+    }
+  }
+
+  // 2. nodes = maximal non-branching runs; flat order = node after node
+  std::vector<int32_t> flat(n_blocks), node_of(n_blocks);
+  std::vector<SkvNode> nodes(1, SkvNode{0, 0, 0, 0});
+  std::vector<int32_t> head_of_node(1, -1);
+  int32_t next_flat = 0;
+  for (int32_t b = 0; b < n_blocks; ++b) {
+    const bool head = parent[b] < 0 || n_child[parent[b]] != 1;
+    if (!head) continue;
+    SkvNode nd{next_flat, 0, 0, 0};
+    const int32_t id = (int32_t)nodes.size();
+    for (int32_t c = b;; c = only_child[c]) {
+      flat[c] = next_flat++;
+      node_of[c] = id;
+      nd.n_blocks++;
+      if (n_child[c] != 1) break;
+    }
+    nodes.push_back(nd);
+    head_of_node.push_back(b);
+  }
+  const int32_t n_nodes = (int32_t)nodes.size() - 1;
+
+  // 3. child tables at branch points
+  std::vector<int32_t> kids(n_nodes + 1, 0);
+  for (int32_t n = 1; n <= n_nodes; ++n) {
+    int32_t p = parent[head_of_node[n]];
+    kids[p < 0 ? 0 : node_of[p]]++;
+  }
+  size_t n_slots = 0;
+  for (int32_t n = 0; n <= n_nodes; ++n) {
+    nodes[n].tab_off = (int32_t)n_slots;
+    nodes[n].tab_cap = kids[n] ? (int32_t)next_pow2(2u * (uint32_t)kids[n]) : 0;
+    n_slots += (size_t)nodes[n].tab_cap;
+  }
+  if (n_slots > 0x7fffffff) return SKV_ERANGE;
+  std::vector<SkvSlot> slots(n_slots ? n_slots : 1, SkvSlot{0, 0, -1, 0});
+  for (int32_t n = 1; n <= n_nodes; ++n) {
+    const int32_t hb = head_of_node[n];
+    const SkvNode& pn = nodes[parent[hb] < 0 ? 0 : node_of[parent[hb]]];
+    const uint64_t h = bhash[hb];
+    uint32_t s = (uint32_t)h & (uint32_t)(pn.tab_cap - 1);
+    while (slots[pn.tab_off + s].child >= 0) s = (s + 1) & (uint32_t)(pn.tab_cap - 1);
+    slots[pn.tab_off + s] = SkvSlot{(uint32_t)h, (uint32_t)(h >> 32), n, 0};
+  }
+
+  // 4. stage and upload
+  const Layout L = make_layout((size_t)n_blocks, (size_t)n_nodes + 1, n_slots);
+  if (L.total > bytes) return SKV_ENOMEM;
+  std::vector<char> host(L.ctr);  // everything before the counters
+  int32_t* h_tok = (int32_t*)(host.data() + L.tok);
+  int32_t* h_page = (int32_t*)(host.data() + L.page);
+  int32_t* h_meta = (int32_t*)(host.data() + L.meta);
+  int32_t* h_canon = (int32_t*)(host.data() + L.canon);
+  for (int32_t b = 0; b < n_blocks; ++b) {
+    const int32_t f = flat[b], in = src[b];
+    memcpy(h_tok + (size_t)f * 16, d->tokens + (size_t)in * 16, 64);
+    h_page[f] = d->blk_page[in];
+    h_meta[f] = (d->blk_sensitive[in] ? (int32_t)0x80000000 : 0) | d->blk_owner[in];
+    h_canon[f] = in;
+  }
+  memcpy(host.data() + L.nodes, nodes.data(), nodes.size() * sizeof(SkvNode));
+  memcpy(host.data() + L.slots, slots.data(), slots.size() * sizeof(SkvSlot));
+
+  skv_tree* t = new (std::nothrow) skv_tree();
+  if (!t) return SKV_EINVAL;
+  char* base = (char*)d_slab;
+  t->dev.tok = (const int32_t*)(base + L.tok);
+  t->dev.page = (const int32_t*)(base + L.page);
+  t->dev.meta = (const int32_t*)(base + L.meta);
+  t->dev.canon = (const int32_t*)(base + L.canon);
+  t->dev.ctr = (uint32_t*)(base + L.ctr);
+  t->dev.nodes = (const SkvNode*)(base + L.nodes);
+  t->dev.slots = (const SkvSlot*)(base + L.slots);
+  t->dev.n_blocks = n_blocks;
+  t->dev.n_nodes = n_nodes;
+  t->dev.n_tenants = d->n_tenants;
+  t->dev.n_pages = d->n_pages;
+  t->n_in_blocks = nib;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = hipGetDevice(&t->device);
+  if (e == hipSuccess && L.ctr) e = hipMemcpyAsync(base, host.data(), L.ctr, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess && n_blocks) {
+    size_t n = (size_t)n_blocks * SKV_CTR_STRIDE;
+    fill_u32_kernel<<<grid_for(n, 256), 256, 0, st>>>(t->dev.ctr, n, 0u);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) {
+    skv_set_hip_error((int)e);
+    delete t;
+    return SKV_EHIP;
+  }
+  *out = t;
+  return SKV_OK;
+}
+
+extern "C" int skv_tree_info(const skv_tree* t, int64_t* n_nodes, int64_t* n_blocks, int64_t* n_in_blocks) {
+  if (!t) return SKV_EINVAL;
+  if (n_nodes) *n_nodes = t->dev.n_nodes;
+  if (n_blocks) *n_blocks = t->dev.n_blocks;
+  if (n_in_blocks) *n_in_blocks = t->n_in_blocks;
+  return SKV_OK;
+}
+
+extern "C" void skv_tree_destroy(skv_tree* t) { delete t; }
+
+extern "C" int skv_counters_read(skv_tree* t, uint32_t* d_hit, uint32_t* d_ucnt, void* stream) {
+  if (!t || !d_hit || !d_ucnt) return SKV_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  if (t->n_in_blocks) {
+    fill_u32_kernel<<<grid_for((size_t)t->n_in_blocks, 256), 256, 0, st>>>(d_hit, (size_t)t->n_in_blocks, 0u);
+    fill_u32_kernel<<<grid_for((size_t)t->n_in_blocks, 256), 256, 0, st>>>(d_ucnt, (size_t)t->n_in_blocks, 0u);
+  }
+  if (t->dev.n_blocks)
+    counters_scatter_kernel<<<grid_for((size_t)t->dev.n_blocks, 256), 256, 0, st>>>(t->dev, d_hit, d_ucnt);
+  SKV_HIP(hipGetLastError());
+  return SKV_OK;
+}
+
+extern "C" int skv_counters_reset(skv_tree* t, void* stream) {
+  if (!t) return SKV_EINVAL;
+  size_t n = (size_t)t->dev.n_blocks * SKV_CTR_STRIDE;
+  if (n) fill_u32_kernel<<<grid_for(n, 256), 256, 0, (hipStream_t)stream>>>(t->dev.ctr, n, 0u);
+  SKV_HIP(hipGetLastError());
+  return SKV_OK;
+}

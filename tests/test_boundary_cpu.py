@@ -1,0 +1,111 @@
+"""The C-ABI library without a GPU: it loads, exports every symbol the header declares, and
+rejects malformed arguments before any device work."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def skv():
+    from paper_2508_08438_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2508_08438_amd.build import build_lib
+        build_lib()
+    binding.lib()
+    return binding
+
+
+def test_library_exports_every_declared_symbol(skv):
+    header = open(os.path.join(ROOT, "include", "skv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(skv_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(skv.EXPORTS)
+    for name in declared:
+        assert hasattr(skv.lib(), name), name
+
+
+def test_error_strings(skv):
+    l = skv.lib()
+    assert l.skv_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert len(l.skv_strerror(code)) > 0
+
+
+def _desc_args(n_blocks=4, n_tenants=3, n_pages=8):
+    tokens = np.arange(n_blocks * 16, dtype=np.int32)
+    return dict(seq_tokens=tokens, seq_off=np.array([0, n_blocks * 16]), blk_sensitive=np.zeros(n_blocks),
+                blk_owner=np.zeros(n_blocks), blk_page=np.arange(n_blocks), n_tenants=n_tenants, n_pages=n_pages)
+
+
+def test_tree_desc_validation(skv):
+    ok = skv.skv_tree_build_size(**_desc_args())
+    assert ok > 0 and ok % 256 == 0
+    assert skv.skv_tree_build_size(**_desc_args(n_blocks=0)) > 0
+
+    def bad(code, **kw):
+        a = _desc_args()
+        a.update(kw)
+        with pytest.raises(skv.SkvError) as e:
+            skv.skv_tree_build_size(**a)
+        assert e.value.code == code
+
+    bad(-1, block_tokens=32)
+    bad(-3, n_tenants=129)
+    bad(-3, n_tenants=0)
+    bad(-1, n_pages=0)
+    bad(-1, seq_off=np.array([0, 60]))          # not a multiple of 16
+    bad(-1, seq_off=np.array([0, 64, 32]))      # decreasing
+    bad(-1, seq_off=np.array([16, 64]))         # does not start at 0
+
+
+def test_build_rejects_bad_blocks_before_touching_the_device(skv):
+    l = skv.lib()
+    out = C.c_void_p()
+    fake_slab = C.c_void_p(256 * 1024)  # never dereferenced: validation fails first
+
+    def rc(**kw):
+        a = _desc_args()
+        a.update(kw)
+        d, keep = skv._tree_desc(**a)
+        return l.skv_tree_build(C.byref(d), fake_slab, 1 << 20, None, C.byref(out))
+
+    assert rc(blk_owner=np.array([0, 3, 0, 0])) == -1      # owner outside [0, n_tenants)
+    assert rc(blk_owner=np.array([0, -1, 0, 0])) == -1
+    assert rc(blk_page=np.array([0, 1, 8, 2])) == -1       # page outside [0, n_pages)
+    assert rc(blk_page=np.array([0, 1, 1, 2])) == -1       # one page backing two cached blocks
+    d, keep = skv._tree_desc(**_desc_args())
+    assert l.skv_tree_build(C.byref(d), C.c_void_p(256 * 1024 + 8), 1 << 20, None, C.byref(out)) == -1  # misaligned
+    assert l.skv_tree_build(C.byref(d), None, 1 << 20, None, C.byref(out)) == -1
+    assert l.skv_tree_build(C.byref(d), fake_slab, 64, None, C.byref(out)) == -2  # slab too small
+    assert l.skv_tree_build(None, fake_slab, 64, None, C.byref(out)) == -1
+
+
+def test_attention_and_gather_argument_checks(skv):
+    import torch
+    l = skv.lib()
+    n = C.c_size_t()
+    for bad in (skv.attn_desc(8, 3, 128, "bf16"), skv.attn_desc(8, 2, 64, "bf16"), skv.attn_desc(8, 2, 96, "f32"),
+                skv.AttnDesc(8, 2, 128, 7, 1.0)):
+        assert l.skv_prefill_attn_workspace_size(C.byref(bad), 4, 100, C.byref(n)) == -1
+    good = skv.attn_desc(32, 8, 128, torch.bfloat16)
+    assert l.skv_prefill_attn_workspace_size(C.byref(good), 4, 1000, C.byref(n)) == 0 and n.value >= 256
+    assert l.skv_prefill_attn_workspace_size(C.byref(good), -1, 1000, C.byref(n)) == -1
+    args = [None] * 4 + [100, None, None, 8, None, None, 4, None, None, 0, None]
+    assert l.skv_prefill_attn(C.byref(good), 4, *args) == -1          # null tensors
+    assert l.skv_prefill_attn(C.byref(good), 0, *args) == 0           # empty batch: nothing to do
+    assert l.skv_gather_kv(C.byref(good), 4, None, None, 8, None, None, 4, None, None, None, 0, None) == -1
+    assert l.skv_match(None, 1, None, None, None, 1, None, None, None) == -1
+    assert l.skv_counters_reset(None, None) == -1
+    assert l.skv_suffix_offsets(2, None, None, None, None) == -1
+
+
+def test_no_fallback_when_library_is_missing(skv, monkeypatch):
+    monkeypatch.setattr(skv, "_lib", None)
+    monkeypatch.setattr(skv, "LIB_PATH", "/nonexistent/libskv.so")
+    with pytest.raises(RuntimeError):
+        skv.lib()

@@ -1,0 +1,251 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Integers (matched lengths, page ids, counters, gathered bytes) must be bit-exact;
+attention must agree within max-abs 1e-4 (fp32) / 2e-2 (bf16) with the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2508_08438_amd import inputs
+from paper_2508_08438_amd.inputs import BLOCK as B
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def _skv():
+    from paper_2508_08438_amd import binding
+    return binding
+
+
+def _session(w, **kw):
+    from paper_2508_08438_amd.pipeline import Session
+    return Session(w, device="cuda:0", **kw)
+
+
+def check_match(w, label):
+    print(f"[match] {label}: R={w.n_req} in_blocks={w.n_in_blocks}", flush=True)
+    s = _session(w, with_kv=False)
+    s.match()
+    torch.cuda.synchronize()
+    tree = oracle.OracleTree.from_workload(w)
+    mb = max(w.max_blocks, 1)
+    mlen, pt = tree.match(w.req_off, w.req_tokens, w.req_tenant, mb)
+    hit, ucnt = tree.counters()
+    info = s.tree.info()
+    assert info["n_blocks"] == tree.n_blocks and info["n_in_blocks"] == w.n_in_blocks
+    assert info["n_nodes"] <= tree.n_nodes  # runs that grew past an old leaf are merged here
+    assert np.array_equal(s.matched_len.cpu().numpy(), mlen), label
+    assert np.array_equal(s.page_table.cpu().numpy(), pt), label
+    g_hit, g_ucnt = s.counters()
+    assert np.array_equal(g_hit, hit) and np.array_equal(g_ucnt, ucnt), label
+    q_off = np.concatenate([[0], np.cumsum(np.diff(w.req_off) - mlen)]).astype(np.int32)
+    assert np.array_equal(s.q_off.cpu().numpy(), q_off)
+    # a second batch in the same window accumulates; reset starts a new window
+    skv = _skv()
+    skv.skv_match(s.tree, s.req_off, s.req_tokens, s.req_tenant, s.max_blocks, s.matched_len, s.page_table)
+    h2, u2 = s.counters()
+    assert np.array_equal(h2, 2 * hit) and np.array_equal(u2, ucnt)
+    skv.skv_counters_reset(s.tree)
+    h3, u3 = s.counters()
+    assert h3.sum() == 0 and u3.sum() == 0
+    return s, mlen, pt
+
+
+def test_match_small_collision_heavy_cases():
+    for seed in range(120):
+        kw = dict(seed=seed, vocab=2 + seed % 2, n_tenants=1 + seed % 3, p_sens=[0.0, 0.3, 0.6, 1.0][seed % 4],
+                  block_vocab=(3 if seed % 5 == 0 else None), n_req=24)
+        check_match(inputs.small_random(**kw), f"small{seed}")
+
+
+def test_match_many_tenants_and_wide_root():
+    # 128 tenants (all four bitmap words), hundreds of root children (multi-round probing)
+    w = inputs.config5(0.5, n_prefix=600, n_req=300, len_lo=16, len_hi=700, suf_lo=0, suf_hi=40)
+    check_match(w, "wide_root")
+
+
+def test_match_empty_tree_and_empty_batch():
+    skv = _skv()
+    w = inputs.small_random(seed=1)
+    w.seq_tokens, w.seq_off = np.zeros(0, np.int32), np.zeros(1, np.int64)
+    w.blk_sensitive, w.blk_owner, w.blk_page = np.zeros(0, np.uint8), np.zeros(0, np.int32), np.zeros(0, np.int32)
+    s, mlen, _ = check_match(w, "empty_tree")
+    assert mlen.sum() == 0
+    z = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    skv.skv_match(s.tree, z, z, z[:0], 4, z, z)  # n_req = 0: no-op
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_match_configs_full_size(name):
+    if name == "c5":
+        prev = None
+        for p in (0.0, 0.25, 0.5, 1.0):
+            _, mlen, _ = check_match(inputs.config5(p), f"c5@{p}")
+            if prev is not None:
+                assert (mlen <= prev).all()
+            prev = mlen
+    else:
+        w = inputs.CONFIGS[name]()
+        _, mlen, _ = check_match(w, name)
+        if name == "c4":
+            assert (mlen == np.diff(w.seq_off)).all()
+            check_match(inputs.config4(literal=True), "c4_literal")
+
+
+def sample_rows(w, mlen, n, seed=0):
+    """(request, head, position) triples: always the first/last rows and the rows next to tile,
+    page and prefix boundaries, then uniform random ones."""
+    g = np.random.default_rng(seed)
+    S = np.diff(w.req_off) - mlen
+    rows = []
+    live = [r for r in range(w.n_req) if S[r] > 0]
+    for r in live[: max(1, n // 64)]:
+        for i in {0, 1, 15, 16, 31, 32, 63, 64, 65, 127, 128, S[r] - 2, S[r] - 1}:
+            if 0 <= i < S[r]:
+                rows.append((r, int(g.integers(0, w.attn.n_q_heads)), int(i)))
+    while len(rows) < n:
+        r = live[int(g.integers(0, len(live)))]
+        rows.append((r, int(g.integers(0, w.attn.n_q_heads)), int(g.integers(0, S[r]))))
+    a = np.array(rows[:n], dtype=np.int32)
+    return a[:, 0].copy(), a[:, 1].copy(), a[:, 2].copy()
+
+
+def check_pipeline(w, label, n_sample=None, threads=16):
+    print(f"[pipeline] {label}", flush=True)
+    s = _session(w)
+    res = s.step()
+    torch.cuda.synchronize()
+    tree = oracle.OracleTree.from_workload(w)
+    mlen, pt = tree.match(w.req_off, w.req_tokens, w.req_tenant, max(w.max_blocks, 1))
+    assert np.array_equal(res["matched_len"].cpu().numpy(), mlen)
+    assert np.array_equal(res["page_table"].cpu().numpy(), pt)
+    kpool, vpool = s.host_pools(pt)
+    # gather: byte-exact
+    kc, vc = oracle.gather(kpool, vpool, mlen, pt)
+    n = kc.shape[0]
+    assert np.array_equal(res["ctx_off"].cpu().numpy(), np.concatenate([[0], np.cumsum(mlen)]))
+    bits = torch.int32 if w.attn.dtype == "f32" else torch.int16
+    assert torch.equal(res["kctx"][:n].cpu().view(bits), kc.view(bits))
+    assert torch.equal(res["vctx"][:n].cpu().view(bits), vc.view(bits))
+    # attention
+    q_off = np.concatenate([[0], np.cumsum(np.diff(w.req_off) - mlen)]).astype(np.int32)
+    q, kn, vn = (w.suffix_rows(x, mlen) for x in "qkv")
+    got = res["out"].double().cpu().numpy()
+    if n_sample is None:
+        want = oracle.attention(q, kn, vn, q_off, kpool, vpool, mlen, pt, scale=w.attn.scale, n_threads=threads)
+        err = np.abs(got - want)
+        ref = np.abs(want).max()
+    else:
+        rows = sample_rows(w, mlen, n_sample)
+        want = oracle.attention(q, kn, vn, q_off, kpool, vpool, mlen, pt, scale=w.attn.scale, rows=rows,
+                                n_threads=threads)
+        pick = got[q_off[rows[0]] + rows[2], rows[1]]
+        err = np.abs(pick - want)
+        ref = np.abs(want).max()
+    print(f"   max-abs err {err.max():.3e}  (|ref| max {ref:.3e}, rel {err.max() / ref:.3e})", flush=True)
+    assert err.max() <= TOL[w.attn.dtype], (label, err.max())
+    return err.max(), ref
+
+
+def test_pipeline_config1_fp32_full():
+    check_pipeline(inputs.config1(), "c1")
+    check_pipeline(inputs.config1(hard=True), "c1_hard")
+
+
+def test_pipeline_config2_bf16_sampled():
+    check_pipeline(inputs.config2(), "c2", n_sample=4096)
+    err, ref = check_pipeline(inputs.config2(hard=True), "c2_hard", n_sample=4096)
+    assert err / ref < 2e-2  # N(0,1) inputs: the relative error has to be small too
+
+
+# ---- attention alone, on shapes the configs do not reach ---------------------------------------
+def attn_case(seed, R, Hq, Hkv, d, dtype, max_blocks, S_list, k_list, n_pages=64, sigma=1.0):
+    g = np.random.default_rng(seed)
+    S = np.asarray(S_list)
+    k_blocks = np.asarray(k_list)
+    perm = g.permutation(n_pages)
+    pt = np.full((R, max_blocks), -1, np.int32)
+    used = 0
+    for r in range(R):
+        pt[r, : k_blocks[r]] = perm[used: used + k_blocks[r]]
+        used += k_blocks[r]
+    q_off = np.concatenate([[0], np.cumsum(S)]).astype(np.int32)
+    T = int(q_off[-1])
+    t = lambda *s: torch.from_numpy(g.standard_normal(s).astype(np.float32) * sigma).to(dtype)
+    return dict(q=t(T, Hq, d), knew=t(T, Hkv, d), vnew=t(T, Hkv, d), q_off=q_off,
+                kpool=t(n_pages, B, Hkv, d), vpool=t(n_pages, B, Hkv, d),
+                matched_len=(k_blocks * B).astype(np.int32), page_table=pt)
+
+
+def run_attn(c, scale=None):
+    skv = _skv()
+    dev = "cuda:0"
+    q = c["q"].to(dev)
+    Hq, d = q.shape[1], q.shape[2]
+    Hkv = c["kpool"].shape[2]
+    desc = skv.attn_desc(Hq, Hkv, d, q.dtype, scale)
+    R = len(c["matched_len"])
+    ws = torch.zeros(skv.skv_prefill_attn_workspace_size(desc, R, q.shape[0]), dtype=torch.uint8, device=dev)
+    out = torch.full_like(q, 7.0)
+    pt = torch.from_numpy(c["page_table"]).to(dev)
+    skv.skv_prefill_attn(desc, q, c["knew"].to(dev), c["vnew"].to(dev), torch.from_numpy(c["q_off"]).to(dev),
+                         c["kpool"].to(dev), c["vpool"].to(dev), torch.from_numpy(c["matched_len"]).to(dev),
+                         pt, pt.shape[1], out, ws)
+    torch.cuda.synchronize()
+    return out.double().cpu().numpy()
+
+
+ATTN_SHAPES = [
+    # Hq, Hkv, d, dtype, S per request, matched blocks per request
+    (8, 2, 128, torch.bfloat16, [1, 63, 64, 65, 0, 200], [0, 1, 3, 4, 5, 9]),     # G=4, ragged tails, S=0
+    (8, 1, 128, torch.bfloat16, [130, 17], [7, 0]),                               # G=8: two head groups
+    (4, 2, 128, torch.bfloat16, [300, 5, 129], [2, 11, 0]),                       # G=2: 2 heads x 2 position tiles
+    (3, 3, 128, torch.bfloat16, [257, 1, 64], [0, 5, 8]),                         # G=1: 4 position tiles
+    (16, 8, 128, torch.bfloat16, [70, 33], [3, 6]),                               # Hkv=8: per-XCD head placement
+    (4, 2, 64, torch.float32, [1, 50, 0, 70], [0, 2, 3, 6]),
+    (2, 1, 128, torch.float32, [40, 9], [1, 4]),
+]
+
+
+@pytest.mark.parametrize("case", range(len(ATTN_SHAPES)))
+def test_attention_shapes_and_ragged_edges(case):
+    Hq, Hkv, d, dtype, S, k = ATTN_SHAPES[case]
+    c = attn_case(100 + case, len(S), Hq, Hkv, d, dtype, max(k) + 1, S, k, sigma=1.0)
+    print(f"[attn] case {case}: Hq={Hq} Hkv={Hkv} d={d} {dtype} S={S} k={k}", flush=True)
+    got = run_attn(c)
+    want = oracle.attention(**c, n_threads=8)
+    n = want.shape[0]
+    err = np.abs(got[:n] - want).max()
+    print(f"   max-abs err {err:.3e}", flush=True)
+    assert err <= (1e-4 if dtype == torch.float32 else 2e-2)
+
+
+def test_attention_closed_forms_on_gpu():
+    """The oracle's closed-form pins, applied to the GPU path directly: V == 1 gives 1; K == 0 with
+    V = position gives (L+i)/2 (bf16 holds integers up to 256 exactly)."""
+    S, k = [100, 37], [4, 0]
+    c = attn_case(5, 2, 8, 2, 128, torch.bfloat16, 5, S, k)
+    c["vpool"].fill_(1.0); c["vnew"].fill_(1.0)
+    assert np.abs(run_attn(c) - 1.0).max() <= 1e-2
+    c["kpool"].zero_(); c["knew"].zero_()
+    for r in range(2):
+        L = int(c["matched_len"][r])
+        for j in range(L):
+            c["vpool"][c["page_table"][r, j // B], j % B] = float(j)
+        for i in range(S[r]):
+            c["vnew"][c["q_off"][r] + i] = float(L + i)
+    got = run_attn(c)
+    for r in range(2):
+        L = int(c["matched_len"][r])
+        for i in range(S[r]):
+            assert np.abs(got[c["q_off"][r] + i] - (L + i) / 2.0).max() <= 0.5 + 1e-6, (r, i)
+
+
+def test_error_codes_need_no_launch():
+    skv = _skv()
+    desc = skv.attn_desc(8, 3, 128, torch.bfloat16)
+    with pytest.raises(skv.SkvError):
+        skv.skv_prefill_attn_workspace_size(desc, 1, 1)
