@@ -28,9 +28,12 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kD = 128;          // head dim of the bf16 kernel
-constexpr int kBN = 64;          // keys per tile
-constexpr int kRowsPerWave = 64; // query rows per wavefront
-constexpr int kWaves = 4;
+constexpr int kBN = 64;          // keys per LDS tile
+constexpr int kStages = 2;       // LDS stages per operand
+constexpr float kRescaleLog2 = 8.f;  // move the softmax reference when a row maximum exceeds it by 2^8
+constexpr int kRowsPerWave = 32; // query rows per wavefront
+constexpr int kWaves = 8;        // two per SIMD: one wave's softmax overlaps the other's MFMAs
+constexpr int kThreads = kWaves * 64;
 constexpr int kKsStride = kD + 8;    // bf16 elements per K row in LDS (272 B: conflict-free b128 reads)
 constexpr int kVtStride = kBN + 8;   // bf16 elements per V^T row in LDS (144 B)
 constexpr float kLog2e = 1.4426950408889634f;
@@ -85,48 +88,47 @@ __global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_of
 
 // ---- bf16 MFMA kernel --------------------------------------------------------------------------
 struct RowSrc {          // where one 16-key group of a tile lives
-  const __bf16* k;       // first row of the group for this kv head (nullptr: no data)
+  const __bf16* k;       // first row of the group for this kv head (always a readable address)
   const __bf16* v;
-  int n_valid;           // rows of the group that exist (0..16)
+  int n_valid;           // rows of the group that exist (0..16); rows beyond are read as zeros
 };
 
+// Branch-free: a group without data (past the end, or a page id outside the pool) points at the
+// request's first new row, which always exists, and reports zero valid rows.
 __device__ inline RowSrc group_source(const AttnParams& p, int r, int kvh, int L, int Ltot, int qbase, int key0) {
-  RowSrc s{nullptr, nullptr, 0};
-  if (key0 >= Ltot) return s;
-  if (key0 < L) {
-    const int page = p.page_table[(size_t)r * p.max_blocks + key0 / SKV_BLOCK_TOKENS];
-    if (page < 0 || page >= p.n_pages) return s;
-    const size_t off = ((size_t)page * SKV_BLOCK_TOKENS * p.Hkv + kvh) * kD;
-    s.k = (const __bf16*)p.kpool + off;
-    s.v = (const __bf16*)p.vpool + off;
-    s.n_valid = 16;
-  } else {
-    const size_t off = ((size_t)(qbase + key0 - L) * p.Hkv + kvh) * kD;
-    s.k = (const __bf16*)p.knew + off;
-    s.v = (const __bf16*)p.vnew + off;
-    s.n_valid = min(16, Ltot - key0);
-  }
+  const bool in_prefix = key0 < L;
+  const int slot = in_prefix ? key0 / SKV_BLOCK_TOKENS : 0;
+  const int page = p.max_blocks > 0 ? p.page_table[(size_t)r * p.max_blocks + min(slot, p.max_blocks - 1)] : -1;
+  const bool page_ok = page >= 0 && page < p.n_pages;
+  const bool is_new = !in_prefix && key0 < Ltot;
+  const size_t off_pool = ((size_t)(page_ok ? page : 0) * SKV_BLOCK_TOKENS * p.Hkv + kvh) * kD;
+  const size_t off_new = ((size_t)(qbase + (is_new ? key0 - L : 0)) * p.Hkv + kvh) * kD;
+  const bool use_pool = in_prefix && page_ok;
+  RowSrc s;
+  s.k = (use_pool ? (const __bf16*)p.kpool + off_pool : (const __bf16*)p.knew + off_new);
+  s.v = (use_pool ? (const __bf16*)p.vpool + off_pool : (const __bf16*)p.vnew + off_new);
+  s.n_valid = use_pool ? 16 : (is_new ? min(16, Ltot - key0) : 0);
   return s;
 }
 
 __device__ inline uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
 __device__ inline uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
-__global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnParams p) {
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[kBN * kKsStride];
-  __shared__ __attribute__((aligned(16))) __bf16 Vt[kD * kVtStride];
+__global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
+  __shared__ __attribute__((aligned(16))) __bf16 smem[kStages * (kBN * kKsStride + kD * kVtStride)];
+  __bf16* const Ks = smem;                               // [kStages][kBN][kKsStride]
+  __bf16* const Vt = smem + kStages * kBN * kKsStride;    // [kStages][kD][kVtStride]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
   const int l32 = lane & 31;
   const int half = lane >> 5;
 
   // ---- which piece of work: XCD-aware decode (workgroup b runs on XCD b % 8) ----
   const int G = p.Hq / p.Hkv;
   const int n_hg = G / p.heads_per_wg;               // head groups per kv head
-  const int pos_tiles = kWaves / p.heads_per_wg;     // 64-row position tiles per workgroup
-  const int pos_per_wg = pos_tiles * kRowsPerWave;
+  const int pos_per_wg = (kWaves / p.heads_per_wg) * kRowsPerWave;
   int item, kvh, hg;
   {
     const int b = blockIdx.x;
@@ -155,208 +157,198 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnParams p) {
 
   const int head = kvh * G + hg * p.heads_per_wg + (wave % p.heads_per_wg);
   const int pos0 = qt * pos_per_wg + (wave / p.heads_per_wg) * kRowsPerWave;  // first row of this wave
-  const bool wave_active = pos0 < S;
   const int wg_pos_end = min(S, (qt + 1) * pos_per_wg);
-  const int n_tiles = (L + wg_pos_end + kBN - 1) / kBN;
-  const int wave_key_end = L + min(S, pos0 + kRowsPerWave);  // keys this wave needs: [0, wave_key_end)
+  const int n_tiles = (L + wg_pos_end + kBN - 1) / kBN;                      // 64-key tiles the workgroup streams
+  const int wave_key_end = pos0 < S ? L + min(S, pos0 + kRowsPerWave) : 0;    // this wave needs keys [0, wave_key_end)
 
-  // ---- Q fragments (B operand of S^T = K Q^T): lane holds query l32 (+32 nt), d = 16 ks + 8 half .. +7
-  bf16x8 qf[2][8];
-#pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
-    int row = pos0 + nt * 32 + l32;
-    row = min(row, S - 1);
-    row = max(row, 0);
+  // ---- Q fragments (B operand of S^T = K Q^T): lane holds query l32, d = 16 ks + 8 half .. +7
+  bf16x8 qf[8];
+  {
+    const int row = max(min(pos0 + l32, S - 1), 0);
     const __bf16* src = (const __bf16*)p.q + ((size_t)(qbase + row) * p.Hq + head) * kD + 8 * half;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[nt][ks] = *(const bf16x8*)(src + ks * 16);
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8*)(src + ks * 16);
   }
 
-  f32x16 o[4][2];
+  f32x16 o[4];   // O^T accumulators: d = 32 a + 8(e/4) + 4 half + e%4, query = l32
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[a][b][i] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY};
-  float l_run[2] = {0.f, 0.f};
+    for (int e = 0; e < 16; ++e) o[a][e] = 0.f;
+  float m_ref = -INFINITY;  // reference maximum the exponentials are taken against (raw score units)
+  float l_run = 0.f;        // running row sum over this lane-half's keys
   const float c = p.scale * kLog2e;
+  const float thr = kRescaleLog2 / c;  // raw-score distance above the reference that forces a rescale
 
-  // staging registers for the next tile
-  u32x4 kreg[4];
-  u32x2 vreg[2][4];
-  const size_t row_stride = (size_t)p.Hkv * kD;
+  // ---- global -> register staging -> LDS ----
+  // A tile is four 16-key groups; a group is one page of the pool or 16 consecutive new rows, so
+  // its base address is wave-uniform (scalar) and each thread adds a fixed offset.
+  u32x4 kreg[2];
+  u32x2 vreg[4];
+  const unsigned row_bytes = (unsigned)p.Hkv * kD * 2u;
+  const int k_row = (tid >> 4) & 15;                         // K: 16 threads x 16 B per key row
+  const unsigned k_toff = (unsigned)k_row * row_bytes + (unsigned)(tid & 15) * 16u;
+  const int k_grp = wave >> 2;                               // + 2 cc: the 16-key group of chunk cc
+  const int v_row0 = ((tid >> 5) & 3) * 4;                   // V: 4 consecutive keys x 4 consecutive d
+  const unsigned v_toff = (unsigned)v_row0 * row_bytes + (unsigned)(tid & 31) * 8u;
+  const int v_grp = wave >> 1;
 
-  auto load_tile = [&](int kt) {
+  auto load_tile = [&](int kt) __attribute__((always_inline)) {
     const int key_base = kt * kBN;
-    // K: chunk cc covers keys 16cc..16cc+15; 16 threads x 16 B per key row
 #pragma unroll
-    for (int cc = 0; cc < 4; ++cc) {
-      const RowSrc g = group_source(p, r, kvh, L, Ltot, qbase, key_base + cc * 16);
-      const int row = tid >> 4, part = tid & 15;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (row < g.n_valid) v = *(const u32x4*)(g.k + (size_t)row * row_stride + part * 8);
-      kreg[cc] = v;
+    for (int cc = 0; cc < 2; ++cc) {
+      const RowSrc g = group_source(p, r, kvh, L, Ltot, qbase, key_base + (cc * 2 + k_grp) * 16);
+      if (g.n_valid == 16) {
+        kreg[cc] = *(const u32x4*)((const char*)g.k + k_toff);
+      } else {  // ragged end of the sequence or a page id outside the pool: missing rows read as zeros
+        const bool ok = k_row < g.n_valid;
+        const u32x4 v = *(const u32x4*)((const char*)g.k + (ok ? k_toff : (unsigned)(tid & 15) * 16u));
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        kreg[cc] = ok ? v : z;
+      }
     }
-    // V: task = 4 consecutive keys x 4 consecutive d; tasks tid and tid + 256
+    {
+      const RowSrc g = group_source(p, r, kvh, L, Ltot, qbase, key_base + v_grp * 16);
+      if (g.n_valid == 16) {
 #pragma unroll
-    for (int c2 = 0; c2 < 2; ++c2) {
-      const int task = tid + 256 * c2;
-      const int dq = task & 31, kq = task >> 5;  // kq in 0..15: keys 4kq..4kq+3
-      const RowSrc g = group_source(p, r, kvh, L, Ltot, qbase, key_base + (kq >> 2) * 16);
+        for (int e = 0; e < 4; ++e) vreg[e] = *(const u32x2*)((const char*)g.v + v_toff + e * row_bytes);
+      } else {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int row = (kq & 3) * 4 + e;
-        u32x2 v = {0u, 0u};
-        if (row < g.n_valid) v = *(const u32x2*)(g.v + (size_t)row * row_stride + dq * 4);
-        vreg[c2][e] = v;
+        for (int e = 0; e < 4; ++e) {
+          const bool ok = v_row0 + e < g.n_valid;
+          const u32x2 v = *(const u32x2*)((const char*)g.v + (ok ? v_toff + e * row_bytes : (unsigned)(tid & 31) * 8u));
+          const u32x2 z = {0u, 0u};
+          vreg[e] = ok ? v : z;
+        }
       }
     }
   };
-
-  auto store_tile = [&]() {
-#pragma unroll
-    for (int cc = 0; cc < 4; ++cc) {
-      const int row = cc * 16 + (tid >> 4), part = tid & 15;
-      *(u32x4*)(Ks + row * kKsStride + part * 8) = kreg[cc];
-    }
-#pragma unroll
-    for (int c2 = 0; c2 < 2; ++c2) {
-      const int task = tid + 256 * c2;
-      const int dq = task & 31, kq = task >> 5;
-      // LDS key position: inside each 16-key group the order is {0-3, 8-11, 4-7, 12-15}, which is
-      // the order in which the P^T accumulator registers of one lane-half enumerate the keys
-      const int o4 = kq & 3;
-      const int pos = (kq >> 2) * 16 + (o4 & 1) * 8 + (o4 >> 1) * 4;
-      const u32x2 k0 = vreg[c2][0], k1 = vreg[c2][1], k2 = vreg[c2][2], k3 = vreg[c2][3];
-      u32x2 r0 = {pack_lo(k0.x, k1.x), pack_lo(k2.x, k3.x)};
-      u32x2 r1 = {pack_hi(k0.x, k1.x), pack_hi(k2.x, k3.x)};
-      u32x2 r2 = {pack_lo(k0.y, k1.y), pack_lo(k2.y, k3.y)};
-      u32x2 r3 = {pack_hi(k0.y, k1.y), pack_hi(k2.y, k3.y)};
-      __bf16* dst = Vt + (dq * 4) * kVtStride + pos;
-      *(u32x2*)(dst) = r0;
-      *(u32x2*)(dst + kVtStride) = r1;
-      *(u32x2*)(dst + 2 * kVtStride) = r2;
-      *(u32x2*)(dst + 3 * kVtStride) = r3;
-    }
+  // LDS positions are fixed per thread.  V^T key position: inside each 16-key group the order is
+  // {0-3, 8-11, 4-7, 12-15}, the order in which the P^T accumulator registers of one lane-half
+  // enumerate the keys.
+  const int k_lds = (tid >> 4) * kKsStride + (tid & 15) * 8;  // + 32 cc rows
+  const int v_o4 = (tid >> 5) & 3;
+  const int v_lds = ((tid & 31) * 4) * kVtStride + (tid >> 7) * 16 + (v_o4 & 1) * 8 + (v_o4 >> 1) * 4;
+  auto store_tile = [&](int kt) __attribute__((always_inline)) {
+    __bf16* kdst = Ks + (kt % kStages) * (kBN * kKsStride) + k_lds;
+    *(u32x4*)(kdst) = kreg[0];
+    *(u32x4*)(kdst + 32 * kKsStride) = kreg[1];
+    const u32x2 k0 = vreg[0], k1 = vreg[1], k2 = vreg[2], k3 = vreg[3];
+    u32x2 r0 = {pack_lo(k0.x, k1.x), pack_lo(k2.x, k3.x)};
+    u32x2 r1 = {pack_hi(k0.x, k1.x), pack_hi(k2.x, k3.x)};
+    u32x2 r2 = {pack_lo(k0.y, k1.y), pack_lo(k2.y, k3.y)};
+    u32x2 r3 = {pack_hi(k0.y, k1.y), pack_hi(k2.y, k3.y)};
+    __bf16* dst = Vt + (kt % kStages) * (kD * kVtStride) + v_lds;
+    *(u32x2*)(dst) = r0;
+    *(u32x2*)(dst + kVtStride) = r1;
+    *(u32x2*)(dst + 2 * kVtStride) = r2;
+    *(u32x2*)(dst + 3 * kVtStride) = r3;
   };
 
   load_tile(0);
+  store_tile(0);
+  __syncthreads();
   for (int kt = 0; kt < n_tiles; ++kt) {
-    store_tile();
-    __syncthreads();
     if (kt + 1 < n_tiles) load_tile(kt + 1);  // in flight during the math below
-
     const int key_base = kt * kBN;
-    if (wave_active && key_base < wave_key_end) {
-      // ---- S^T = K Q^T : [64 keys][64 queries] as 2x2 tiles of 32x32
-      f32x16 s[2][2];
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) s[a][b][i] = 0.f;
+    if (key_base < wave_key_end) {
+      const __bf16* kb = Ks + (kt % kStages) * (kBN * kKsStride) + l32 * kKsStride + 8 * half;
+      const __bf16* vb = Vt + (kt % kStages) * (kD * kVtStride) + l32 * kVtStride + 8 * half;
+      // ---- S^T = K Q^T : [64 keys][32 queries] as two 32x32 tiles
+      f32x16 s[2];
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
-          const bf16x8 a = *(const bf16x8*)(Ks + (mt * 32 + l32) * kKsStride + ks * 16 + 8 * half);
-          s[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][ks], s[mt][0], 0, 0, 0);
-          s[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][ks], s[mt][1], 0, 0, 0);
+          const bf16x8 a = *(const bf16x8*)(kb + mt * 32 * kKsStride + ks * 16);
+          s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], ks == 0 ? zero : s[mt], 0, 0, 0);
         }
       }
       // ---- causal mask on tiles that reach past the first row's limit
       if (key_base + kBN - 1 > L + pos0) {
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-          const int limit = L + pos0 + nt * 32 + l32;  // last visible key of this lane's query
-#pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int key = key_base + mt * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
-              if (key > limit) s[mt][nt][i] = -INFINITY;
-            }
-        }
-      }
-      // ---- online softmax (per query = per lane column), P^T packed to bf16 B operands
-      bf16x8 pb[2][4];
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt) {
-        float mx = s[0][nt][0];
+        const int limit = L + pos0 + l32;  // last visible key of this lane's query
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[mt][nt][i]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[nt], mx);
-        const float alpha = __builtin_amdgcn_exp2f((m_run[nt] - m_new) * c);
-        const float mc = m_new * c;
-        float sum = 0.f;
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float e = __builtin_amdgcn_exp2f(s[mt][nt][i] * c - mc);
-            s[mt][nt][i] = e;
-            sum += e;
+          for (int e = 0; e < 16; ++e) {
+            const int key = key_base + mt * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
+            if (key > limit) s[mt][e] = -INFINITY;
           }
-        l_run[nt] = l_run[nt] * alpha + sum;
-        m_run[nt] = m_new;
+      }
+      // ---- streaming softmax: the reference maximum only moves when a row maximum exceeds it by
+      // more than 2^kRescaleLog2 (then O and the row sum are rescaled); otherwise exponentials are
+      // taken against the stale reference, which leaves the normalised result unchanged
+      float mx = s[0][0];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[mt][e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      if (__any(mx > m_ref + thr)) {
+        const float m_new = fmaxf(m_ref, mx);
+        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_ref - m_new) * c);
+        m_ref = m_new;
+        l_run *= alpha;
 #pragma unroll
         for (int a = 0; a < 4; ++a)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) o[a][nt][i] *= alpha;
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int q2 = 0; q2 < 2; ++q2) {
-            bf16x8 pk;
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-              f32x2 pr = {s[mt][nt][q2 * 8 + e], s[mt][nt][q2 * 8 + e + 1]};
-              bf16x2 cv = __builtin_convertvector(pr, bf16x2);
-              pk[e] = cv[0];
-              pk[e + 1] = cv[1];
-            }
-            pb[nt][mt * 2 + q2] = pk;
-          }
+          for (int e = 0; e < 16; ++e) o[a][e] *= alpha;
       }
-      // ---- O^T += V^T P^T : [128 d][64 queries]; k-step g16 covers keys 16 g16 .. +15 of the tile
+      const float mc = m_ref * c;
+      bf16x8 pb[4];  // P^T as B operands, one per 16-key group
+      float sum = 0.f;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int q2 = 0; q2 < 2; ++q2) {
+          bf16x8 pk;
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const float e0 = __builtin_amdgcn_exp2f(s[mt][q2 * 8 + e] * c - mc);
+            const float e1 = __builtin_amdgcn_exp2f(s[mt][q2 * 8 + e + 1] * c - mc);
+            sum += e0 + e1;
+            f32x2 pr = {e0, e1};
+            bf16x2 cv = __builtin_convertvector(pr, bf16x2);
+            pk[e] = cv[0];
+            pk[e + 1] = cv[1];
+          }
+          pb[mt * 2 + q2] = pk;
+        }
+      l_run += sum;
+      // ---- O^T += V^T P^T : [128 d][32 queries]; k-step g16 covers keys 16 g16 .. +15 of the tile
 #pragma unroll
       for (int g16 = 0; g16 < 4; ++g16) {
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-          const bf16x8 va = *(const bf16x8*)(Vt + (a * 32 + l32) * kVtStride + g16 * 16 + 8 * half);
-          o[a][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[0][g16], o[a][0], 0, 0, 0);
-          o[a][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[1][g16], o[a][1], 0, 0, 0);
+          const bf16x8 va = *(const bf16x8*)(vb + a * 32 * kVtStride + g16 * 16);
+          o[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[g16], o[a], 0, 0, 0);
         }
       }
     }
-    __syncthreads();  // everyone is done with this tile before it is overwritten
+    // the other stage was last read one iteration ago, before the barrier every wave has passed
+    if (kt + 1 < n_tiles) store_tile(kt + 1);
+    __syncthreads();
   }
 
-  // ---- normalise and store: lane holds query l32 (+32 nt); d = 32 a + 8 (i/4) + 4 half + i%4
-  if (!wave_active) return;
-#pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
-    const float lsum = l_run[nt] + __shfl_xor(l_run[nt], 32);
+  // ---- normalise and store: lane holds query l32; d = 32 a + 8 (e/4) + 4 half + e%4
+  if (pos0 >= S) return;
+  {
+    const float lsum = l_run + __shfl_xor(l_run, 32);
     const float inv = 1.0f / lsum;
-    const int pos = pos0 + nt * 32 + l32;
+    const int pos = pos0 + l32;
     if (pos < S) {
       __bf16* dst = (__bf16*)p.out + ((size_t)(qbase + pos) * p.Hq + head) * kD + 4 * half;
 #pragma unroll
       for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          f32x2 x0 = {o[a][nt][i4 * 4 + 0] * inv, o[a][nt][i4 * 4 + 1] * inv};
-          f32x2 x1 = {o[a][nt][i4 * 4 + 2] * inv, o[a][nt][i4 * 4 + 3] * inv};
+          f32x2 x0 = {o[a][i4 * 4 + 0] * inv, o[a][i4 * 4 + 1] * inv};
+          f32x2 x1 = {o[a][i4 * 4 + 2] * inv, o[a][i4 * 4 + 3] * inv};
           bf16x2 y0 = __builtin_convertvector(x0, bf16x2);
           bf16x2 y1 = __builtin_convertvector(x1, bf16x2);
-          u32x2 w = {__builtin_bit_cast(uint32_t, y0), __builtin_bit_cast(uint32_t, y1)};
-          *(u32x2*)(dst + a * 32 + i4 * 8) = w;
+          u32x2 wv = {__builtin_bit_cast(uint32_t, y0), __builtin_bit_cast(uint32_t, y1)};
+          *(u32x2*)(dst + a * 32 + i4 * 8) = wv;
         }
     }
   }
@@ -445,7 +437,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p, int64_t max_
   }
 }
 
-int heads_per_wg_for(int G) { return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1); }
+int heads_per_wg_for(int G) { return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1); }  // divides kWaves
 
 int check_attn(const skv_attn_desc* d) {
   if (!d) return SKV_EINVAL;
@@ -523,7 +515,7 @@ extern "C" int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const 
   attn_schedule_kernel<<<1, 1024, 0, st>>>(n_req, d_q_off, pos_per_wg, (int)max_items,
                                            (int32_t*)d_workspace, (int32_t*)((char*)d_workspace + 256));
   SKV_HIP(hipGetLastError());
-  attn_bf16_kernel<<<(int)grid, 256, 0, st>>>(p);
+  attn_bf16_kernel<<<(int)grid, kThreads, 0, st>>>(p);
   SKV_HIP(hipGetLastError());
   return SKV_OK;
 }
