@@ -26,16 +26,20 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr int kD = 128;          // head dim of the bf16 kernel
 constexpr int kBN = 64;          // keys per LDS tile
-constexpr int kStages = 2;       // LDS stages per operand
+constexpr int kKStages = 2;      // LDS stages of K
+constexpr int kVStages = 2;      // LDS stages of V
 constexpr float kRescaleLog2 = 8.f;  // move the softmax reference when a row maximum exceeds it by 2^8
 constexpr int kRowsPerWave = 32; // query rows per wavefront
 constexpr int kWaves = 8;        // two per SIMD: one wave's softmax overlaps the other's MFMAs
 constexpr int kThreads = kWaves * 64;
 constexpr int kKsStride = kD + 8;    // bf16 elements per K row in LDS (272 B: conflict-free b128 reads)
-constexpr int kVtStride = kBN + 8;   // bf16 elements per V^T row in LDS (144 B)
+constexpr int kVsStride = kD + 32;    // bf16 elements per V row in LDS (320 B: conflict-free transpose loads)
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct AttnParams {
@@ -93,31 +97,35 @@ struct RowSrc {          // where one 16-key group of a tile lives
   int n_valid;           // rows of the group that exist (0..16); rows beyond are read as zeros
 };
 
-// Branch-free: a group without data (past the end, or a page id outside the pool) points at the
-// request's first new row, which always exists, and reports zero valid rows.
-__device__ inline RowSrc group_source(const AttnParams& p, int r, int kvh, int L, int Ltot, int qbase, int key0) {
-  const bool in_prefix = key0 < L;
-  const int slot = in_prefix ? key0 / SKV_BLOCK_TOKENS : 0;
-  const int page = p.max_blocks > 0 ? p.page_table[(size_t)r * p.max_blocks + min(slot, p.max_blocks - 1)] : -1;
-  const bool page_ok = page >= 0 && page < p.n_pages;
-  const bool is_new = !in_prefix && key0 < Ltot;
-  const size_t off_pool = ((size_t)(page_ok ? page : 0) * SKV_BLOCK_TOKENS * p.Hkv + kvh) * kD;
-  const size_t off_new = ((size_t)(qbase + (is_new ? key0 - L : 0)) * p.Hkv + kvh) * kD;
-  const bool use_pool = in_prefix && page_ok;
+// All arguments are wave-uniform, so this is scalar code.  `page` is the page-table entry of the
+// group when it lies in the reused prefix.  A group without data (past the end, or a page id outside
+// the pool) points at the request's first new row, which always exists, and reports no valid rows.
+__device__ inline RowSrc group_source(const AttnParams& p, int kvh, int L, int Ltot, int qbase, int key0, int page) {
   RowSrc s;
-  s.k = (use_pool ? (const __bf16*)p.kpool + off_pool : (const __bf16*)p.knew + off_new);
-  s.v = (use_pool ? (const __bf16*)p.vpool + off_pool : (const __bf16*)p.vnew + off_new);
-  s.n_valid = use_pool ? 16 : (is_new ? min(16, Ltot - key0) : 0);
+  if (key0 < L && page >= 0 && page < p.n_pages) {
+    const size_t off = ((size_t)page * SKV_BLOCK_TOKENS * p.Hkv + kvh) * kD;
+    s.k = (const __bf16*)p.kpool + off;
+    s.v = (const __bf16*)p.vpool + off;
+    s.n_valid = 16;
+  } else {
+    const bool is_new = key0 >= L && key0 < Ltot;
+    const size_t off = ((size_t)(qbase + (is_new ? key0 - L : 0)) * p.Hkv + kvh) * kD;
+    s.k = (const __bf16*)p.knew + off;
+    s.v = (const __bf16*)p.vnew + off;
+    s.n_valid = is_new ? min(16, Ltot - key0) : 0;
+  }
   return s;
 }
 
-__device__ inline uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
-__device__ inline uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+struct Softmax {
+  float m_ref;   // reference maximum the exponentials are taken against (raw score units)
+  float l_run;   // running row sum over this lane-half's keys
+};
 
 __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
-  __shared__ __attribute__((aligned(16))) __bf16 smem[kStages * (kBN * kKsStride + kD * kVtStride)];
-  __bf16* const Ks = smem;                               // [kStages][kBN][kKsStride]
-  __bf16* const Vt = smem + kStages * kBN * kKsStride;    // [kStages][kD][kVtStride]
+  __shared__ __attribute__((aligned(16))) __bf16 smem[kKStages * kBN * kKsStride + kVStages * kBN * kVsStride];
+  __bf16* const Ks = smem;                                // [kKStages][kBN][kKsStride]
+  __bf16* const Vs = smem + kKStages * kBN * kKsStride;    // [kVStages][kBN][kVsStride]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -175,166 +183,176 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   for (int a = 0; a < 4; ++a)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[a][e] = 0.f;
-  float m_ref = -INFINITY;  // reference maximum the exponentials are taken against (raw score units)
-  float l_run = 0.f;        // running row sum over this lane-half's keys
+  Softmax sm{-INFINITY, 0.f};
   const float c = p.scale * kLog2e;
   const float thr = kRescaleLog2 / c;  // raw-score distance above the reference that forces a rescale
 
   // ---- global -> register staging -> LDS ----
   // A tile is four 16-key groups; a group is one page of the pool or 16 consecutive new rows, so
-  // its base address is wave-uniform (scalar) and each thread adds a fixed offset.
-  u32x4 kreg[2];
-  u32x2 vreg[4];
+  // its base address is wave-uniform (scalar) and each thread adds a fixed offset.  K and V rows go
+  // to LDS as they are (row = key); the PV product reads V through the LDS transpose load.
+  u32x4 kreg[2], vreg[2];
   const unsigned row_bytes = (unsigned)p.Hkv * kD * 2u;
-  const int k_row = (tid >> 4) & 15;                         // K: 16 threads x 16 B per key row
-  const unsigned k_toff = (unsigned)k_row * row_bytes + (unsigned)(tid & 15) * 16u;
-  const int k_grp = wave >> 2;                               // + 2 cc: the 16-key group of chunk cc
-  const int v_row0 = ((tid >> 5) & 3) * 4;                   // V: 4 consecutive keys x 4 consecutive d
-  const unsigned v_toff = (unsigned)v_row0 * row_bytes + (unsigned)(tid & 31) * 8u;
-  const int v_grp = wave >> 1;
+  const int t_row = (tid >> 4) & 15;                         // 16 threads x 16 B per key row
+  const unsigned t_off = (unsigned)t_row * row_bytes + (unsigned)(tid & 15) * 16u;
+  const int t_grp = wave >> 2;                               // + 2 cc: the 16-key group of chunk cc
 
+  // Page ids of the next 64 key groups (16 tiles) sit one per lane in a register; the group's id is
+  // read with a lane broadcast, so no memory latency sits between tiles.  Window w covers tiles
+  // 16w .. 16w+15 and is fetched one iteration before its first use.
+  const int n_prefix_groups = L / SKV_BLOCK_TOKENS;
+  auto fetch_window = [&](int w) __attribute__((always_inline)) {
+    const int gi = w * 64 + lane;
+    int v = -1;
+    if (gi < n_prefix_groups && gi < p.max_blocks) v = p.page_table[(size_t)r * p.max_blocks + gi];
+    return v;
+  };
+  int pt_cur = fetch_window(0), pt_nxt = -1;
   auto load_tile = [&](int kt) __attribute__((always_inline)) {
     const int key_base = kt * kBN;
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc) {
-      const RowSrc g = group_source(p, r, kvh, L, Ltot, qbase, key_base + (cc * 2 + k_grp) * 16);
-      if (g.n_valid == 16) {
-        kreg[cc] = *(const u32x4*)((const char*)g.k + k_toff);
+      const int g = cc * 2 + t_grp;
+      const int page = __builtin_amdgcn_readlane(pt_cur, ((kt & 15) << 2) + g);
+      const RowSrc src = group_source(p, kvh, L, Ltot, qbase, key_base + g * 16, page);
+      if (src.n_valid == 16) {
+        kreg[cc] = *(const u32x4*)((const char*)src.k + t_off);
+        vreg[cc] = *(const u32x4*)((const char*)src.v + t_off);
       } else {  // ragged end of the sequence or a page id outside the pool: missing rows read as zeros
-        const bool ok = k_row < g.n_valid;
-        const u32x4 v = *(const u32x4*)((const char*)g.k + (ok ? k_toff : (unsigned)(tid & 15) * 16u));
+        const bool ok = t_row < src.n_valid;
+        const unsigned off = ok ? t_off : (unsigned)(tid & 15) * 16u;
         const u32x4 z = {0u, 0u, 0u, 0u};
-        kreg[cc] = ok ? v : z;
-      }
-    }
-    {
-      const RowSrc g = group_source(p, r, kvh, L, Ltot, qbase, key_base + v_grp * 16);
-      if (g.n_valid == 16) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) vreg[e] = *(const u32x2*)((const char*)g.v + v_toff + e * row_bytes);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const bool ok = v_row0 + e < g.n_valid;
-          const u32x2 v = *(const u32x2*)((const char*)g.v + (ok ? v_toff + e * row_bytes : (unsigned)(tid & 31) * 8u));
-          const u32x2 z = {0u, 0u};
-          vreg[e] = ok ? v : z;
-        }
+        const u32x4 kv = *(const u32x4*)((const char*)src.k + off);
+        const u32x4 vv = *(const u32x4*)((const char*)src.v + off);
+        kreg[cc] = ok ? kv : z;
+        vreg[cc] = ok ? vv : z;
       }
     }
   };
-  // LDS positions are fixed per thread.  V^T key position: inside each 16-key group the order is
-  // {0-3, 8-11, 4-7, 12-15}, the order in which the P^T accumulator registers of one lane-half
-  // enumerate the keys.
   const int k_lds = (tid >> 4) * kKsStride + (tid & 15) * 8;  // + 32 cc rows
-  const int v_o4 = (tid >> 5) & 3;
-  const int v_lds = ((tid & 31) * 4) * kVtStride + (tid >> 7) * 16 + (v_o4 & 1) * 8 + (v_o4 >> 1) * 4;
-  auto store_tile = [&](int kt) __attribute__((always_inline)) {
-    __bf16* kdst = Ks + (kt % kStages) * (kBN * kKsStride) + k_lds;
-    *(u32x4*)(kdst) = kreg[0];
-    *(u32x4*)(kdst + 32 * kKsStride) = kreg[1];
-    const u32x2 k0 = vreg[0], k1 = vreg[1], k2 = vreg[2], k3 = vreg[3];
-    u32x2 r0 = {pack_lo(k0.x, k1.x), pack_lo(k2.x, k3.x)};
-    u32x2 r1 = {pack_hi(k0.x, k1.x), pack_hi(k2.x, k3.x)};
-    u32x2 r2 = {pack_lo(k0.y, k1.y), pack_lo(k2.y, k3.y)};
-    u32x2 r3 = {pack_hi(k0.y, k1.y), pack_hi(k2.y, k3.y)};
-    __bf16* dst = Vt + (kt % kStages) * (kD * kVtStride) + v_lds;
-    *(u32x2*)(dst) = r0;
-    *(u32x2*)(dst + kVtStride) = r1;
-    *(u32x2*)(dst + 2 * kVtStride) = r2;
-    *(u32x2*)(dst + 3 * kVtStride) = r3;
+  const int v_lds = (tid >> 4) * kVsStride + (tid & 15) * 8;
+  auto store_k = [&](int kt) __attribute__((always_inline)) {
+    __bf16* dst = Ks + (kt % kKStages) * (kBN * kKsStride) + k_lds;
+    *(u32x4*)(dst) = kreg[0];
+    *(u32x4*)(dst + 32 * kKsStride) = kreg[1];
+  };
+  auto store_v = [&](int kt) __attribute__((always_inline)) {
+    __bf16* dst = Vs + (kt % kVStages) * (kBN * kVsStride) + v_lds;
+    *(u32x4*)(dst) = vreg[0];
+    *(u32x4*)(dst + 32 * kVsStride) = vreg[1];
   };
 
-  load_tile(0);
-  store_tile(0);
-  __syncthreads();
-  for (int kt = 0; kt < n_tiles; ++kt) {
-    if (kt + 1 < n_tiles) load_tile(kt + 1);  // in flight during the math below
-    const int key_base = kt * kBN;
-    if (key_base < wave_key_end) {
-      const __bf16* kb = Ks + (kt % kStages) * (kBN * kKsStride) + l32 * kKsStride + 8 * half;
-      const __bf16* vb = Vt + (kt % kStages) * (kD * kVtStride) + l32 * kVtStride + 8 * half;
-      // ---- S^T = K Q^T : [64 keys][32 queries] as two 32x32 tiles
-      f32x16 s[2];
-      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // ---- the three phases of a tile ----
+  f32x16 s[2];   // S^T of the current tile: [64 keys][32 queries] as two 32x32 tiles
+  bf16x8 pb[4];  // P^T as B operands, one per 16-key group
+  // S^T = K Q^T, then the causal mask on tiles that reach past the first row's limit
+  auto qk = [&](int kt) __attribute__((always_inline)) {
+    const __bf16* kb = Ks + (kt % kKStages) * (kBN * kKsStride) + l32 * kKsStride + 8 * half;
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-          const bf16x8 a = *(const bf16x8*)(kb + mt * 32 * kKsStride + ks * 16);
-          s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], ks == 0 ? zero : s[mt], 0, 0, 0);
-        }
-      }
-      // ---- causal mask on tiles that reach past the first row's limit
-      if (key_base + kBN - 1 > L + pos0) {
-        const int limit = L + pos0 + l32;  // last visible key of this lane's query
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int key = key_base + mt * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
-            if (key > limit) s[mt][e] = -INFINITY;
-          }
-      }
-      // ---- streaming softmax: the reference maximum only moves when a row maximum exceeds it by
-      // more than 2^kRescaleLog2 (then O and the row sum are rescaled); otherwise exponentials are
-      // taken against the stale reference, which leaves the normalised result unchanged
-      float mx = s[0][0];
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[mt][e]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      if (__any(mx > m_ref + thr)) {
-        const float m_new = fmaxf(m_ref, mx);
-        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_ref - m_new) * c);
-        m_ref = m_new;
-        l_run *= alpha;
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) o[a][e] *= alpha;
-      }
-      const float mc = m_ref * c;
-      bf16x8 pb[4];  // P^T as B operands, one per 16-key group
-      float sum = 0.f;
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int q2 = 0; q2 < 2; ++q2) {
-          bf16x8 pk;
-#pragma unroll
-          for (int e = 0; e < 8; e += 2) {
-            const float e0 = __builtin_amdgcn_exp2f(s[mt][q2 * 8 + e] * c - mc);
-            const float e1 = __builtin_amdgcn_exp2f(s[mt][q2 * 8 + e + 1] * c - mc);
-            sum += e0 + e1;
-            f32x2 pr = {e0, e1};
-            bf16x2 cv = __builtin_convertvector(pr, bf16x2);
-            pk[e] = cv[0];
-            pk[e + 1] = cv[1];
-          }
-          pb[mt * 2 + q2] = pk;
-        }
-      l_run += sum;
-      // ---- O^T += V^T P^T : [128 d][32 queries]; k-step g16 covers keys 16 g16 .. +15 of the tile
-#pragma unroll
-      for (int g16 = 0; g16 < 4; ++g16) {
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          const bf16x8 va = *(const bf16x8*)(vb + a * 32 * kVtStride + g16 * 16);
-          o[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[g16], o[a], 0, 0, 0);
-        }
+      for (int mt = 0; mt < 2; ++mt) {
+        const bf16x8 a = *(const bf16x8*)(kb + mt * 32 * kKsStride + ks * 16);
+        s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], ks == 0 ? zero : s[mt], 0, 0, 0);
       }
     }
+    const int key_base = kt * kBN;
+    if (key_base + kBN - 1 > L + pos0) {
+      const int limit = L + pos0 + l32;  // last visible key of this lane's query
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int key = key_base + mt * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
+          if (key > limit) s[mt][e] = -INFINITY;
+        }
+    }
+  };
+  // Streaming softmax: the reference maximum only moves when a row maximum exceeds it by more than
+  // 2^kRescaleLog2 (then O and the row sum are rescaled); otherwise exponentials are taken against
+  // the stale reference, which leaves the normalised result unchanged.
+  auto softmax = [&]() __attribute__((always_inline)) {
+    float mx = s[0][0];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[mt][e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    if (__any(mx > sm.m_ref + thr)) {
+      const float m_new = fmaxf(sm.m_ref, mx);
+      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((sm.m_ref - m_new) * c);
+      sm.m_ref = m_new;
+      sm.l_run *= alpha;
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[a][e] *= alpha;
+    }
+    const float mc = sm.m_ref * c;
+    float sum = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int q2 = 0; q2 < 2; ++q2) {
+        bf16x8 pk;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const float e0 = __builtin_amdgcn_exp2f(s[mt][q2 * 8 + e] * c - mc);
+          const float e1 = __builtin_amdgcn_exp2f(s[mt][q2 * 8 + e + 1] * c - mc);
+          sum += e0 + e1;
+          f32x2 pr = {e0, e1};
+          bf16x2 cv = __builtin_convertvector(pr, bf16x2);
+          pk[e] = cv[0];
+          pk[e + 1] = cv[1];
+        }
+        pb[mt * 2 + q2] = pk;
+      }
+    sm.l_run += sum;
+  };
+  // O^T += V^T P^T : [128 d][32 queries].  The A operand wants, per lane (d = 32 a + l32), the eight
+  // keys {4 half + 0..3, 8 + 4 half + 0..3} of a 16-key group -- the keys this lane-half's P^T registers
+  // hold.  Each quad comes from one LDS transpose load: within 16 lanes, lane i supplies the address of
+  // 4 consecutive d of key (i / 4) at d offset 4 (i % 4) and receives d offset i of the four keys.
+  const int v_lane = (4 * half + ((lane & 15) >> 2)) * kVsStride + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  auto pv = [&](int kt) __attribute__((always_inline)) {
+    const __bf16* vb = Vs + (kt % kVStages) * (kBN * kVsStride) + v_lane;
+#pragma unroll
+    for (int g16 = 0; g16 < 4; ++g16) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const __bf16* src = vb + g16 * 16 * kVsStride + a * 32;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + 8 * kVsStride));
+        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        o[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[g16], o[a], 0, 0, 0);
+      }
+    }
+  };
+
+  // ---- main loop: loads of tile kt+1 are in flight during the math on tile kt; one barrier per tile
+  load_tile(0);
+  store_k(0);
+  store_v(0);
+  __syncthreads();
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    if (((kt + 1) & 15) == 0) pt_cur = pt_nxt;
+    if (kt + 1 < n_tiles) load_tile(kt + 1);
+    if (((kt + 2) & 15) == 0) pt_nxt = fetch_window((kt + 2) >> 4);
+    if (kt * kBN < wave_key_end) {
+      qk(kt);
+      softmax();
+      pv(kt);
+    }
     // the other stage was last read one iteration ago, before the barrier every wave has passed
-    if (kt + 1 < n_tiles) store_tile(kt + 1);
+    if (kt + 1 < n_tiles) { store_k(kt + 1); store_v(kt + 1); }
     __syncthreads();
   }
 
   // ---- normalise and store: lane holds query l32; d = 32 a + 8 (e/4) + 4 half + e%4
   if (pos0 >= S) return;
   {
-    const float lsum = l_run + __shfl_xor(l_run, 32);
+    const float lsum = sm.l_run + __shfl_xor(sm.l_run, 32);
     const float inv = 1.0f / lsum;
     const int pos = pos0 + l32;
     if (pos < S) {
