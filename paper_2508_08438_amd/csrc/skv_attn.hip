@@ -242,20 +242,41 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
     *(u32x4*)(dst + 32 * kVsStride) = vreg[1];
   };
 
-  // ---- the three phases of a tile ----
+  // ---- the phases of a tile ----
+  // LDS fragment reads run eight fragments ahead of the MFMAs that consume them (a fragment register
+  // is refilled as soon as its MFMA has been issued), and the first V fragments are requested before
+  // the softmax, so that LDS latency hides behind matrix-core and vector work.
   f32x16 s[2];   // S^T of the current tile: [64 keys][32 queries] as two 32x32 tiles
   bf16x8 pb[4];  // P^T as B operands, one per 16-key group
+  bf16x8 fr[8];  // fragment ring: K fragments during QK, V^T fragments during PV
+  const int k_lane = l32 * kKsStride + 8 * half;
+  // The PV A operand wants, per lane (d = 32 a + l32), the eight keys {4 half + 0..3, 8 + 4 half + 0..3}
+  // of a 16-key group -- the keys this lane-half's P^T registers hold.  Each quad comes from one LDS
+  // transpose load: within 16 lanes, lane i supplies the address of 4 consecutive d of key (i / 4) at d
+  // offset 4 (i % 4) and receives d offset i of the four keys.
+  const int v_lane = (4 * half + ((lane & 15) >> 2)) * kVsStride + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  auto k_frag = [&](const __bf16* kb, int j) __attribute__((always_inline)) {   // fragment j = (ks, mt) = (j / 2, j % 2)
+    return *(const bf16x8*)(kb + (j & 1) * 32 * kKsStride + (j >> 1) * 16);
+  };
+  auto v_frag = [&](const __bf16* vb, int j) __attribute__((always_inline)) {   // fragment j = (g16, a) = (j / 4, j % 4)
+    const __bf16* src = vb + (j >> 2) * 16 * kVsStride + (j & 3) * 32;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + 8 * kVsStride));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
   // S^T = K Q^T, then the causal mask on tiles that reach past the first row's limit
   auto qk = [&](int kt) __attribute__((always_inline)) {
-    const __bf16* kb = Ks + (kt % kKStages) * (kBN * kKsStride) + l32 * kKsStride + 8 * half;
+    const __bf16* kb = Ks + (kt % kKStages) * (kBN * kKsStride) + k_lane;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int j = 0; j < 8; ++j) fr[j] = k_frag(kb, j);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        const bf16x8 a = *(const bf16x8*)(kb + mt * 32 * kKsStride + ks * 16);
-        s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], ks == 0 ? zero : s[mt], 0, 0, 0);
-      }
+    for (int j = 0; j < 16; ++j) {
+      const int ks = j >> 1, mt = j & 1;
+      s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 7], qf[ks], ks == 0 ? zero : s[mt], 0, 0, 0);
+      if (j < 8) fr[j] = k_frag(kb, j + 8);
+      __builtin_amdgcn_sched_barrier(0);
     }
     const int key_base = kt * kBN;
     if (key_base + kBN - 1 > L + pos0) {
@@ -310,23 +331,21 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
       }
     sm.l_run += sum;
   };
-  // O^T += V^T P^T : [128 d][32 queries].  The A operand wants, per lane (d = 32 a + l32), the eight
-  // keys {4 half + 0..3, 8 + 4 half + 0..3} of a 16-key group -- the keys this lane-half's P^T registers
-  // hold.  Each quad comes from one LDS transpose load: within 16 lanes, lane i supplies the address of
-  // 4 consecutive d of key (i / 4) at d offset 4 (i % 4) and receives d offset i of the four keys.
-  const int v_lane = (4 * half + ((lane & 15) >> 2)) * kVsStride + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  // O^T += V^T P^T : [128 d][32 queries]
+  auto pv_prefetch = [&](int kt) __attribute__((always_inline)) {
+    const __bf16* vb = Vs + (kt % kVStages) * (kBN * kVsStride) + v_lane;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) fr[j] = v_frag(vb, j);
+    __builtin_amdgcn_sched_barrier(0);
+  };
   auto pv = [&](int kt) __attribute__((always_inline)) {
     const __bf16* vb = Vs + (kt % kVStages) * (kBN * kVsStride) + v_lane;
 #pragma unroll
-    for (int g16 = 0; g16 < 4; ++g16) {
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const __bf16* src = vb + g16 * 16 * kVsStride + a * 32;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + 8 * kVsStride));
-        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        o[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[g16], o[a], 0, 0, 0);
-      }
+    for (int j = 0; j < 16; ++j) {
+      const int g16 = j >> 2, a = j & 3;
+      o[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 7], pb[g16], o[a], 0, 0, 0);
+      if (j < 8) fr[j] = v_frag(vb, j + 8);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
@@ -341,6 +360,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
     if (((kt + 2) & 15) == 0) pt_nxt = fetch_window((kt + 2) >> 4);
     if (kt * kBN < wave_key_end) {
       qk(kt);
+      pv_prefetch(kt);
       softmax();
       pv(kt);
     }
