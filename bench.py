@@ -29,11 +29,29 @@ def attention_flops(w, mlen):
     return 4.0 * w.attn.head_dim * w.attn.n_q_heads * float((S * L + S * (S + 1) / 2).sum())
 
 
-def cpu_baseline(w, sess, mlen, pt, rows_target, flops_total):
-    """Time the oracle, as it stands, on the host cores: match + gather over the whole batch,
-    attention on a seeded sample of output rows (scaled to the batch by algorithmic flops)."""
+def measured_traffic(workload_key, kernel):
+    """HBM bytes per launch from the committed rocprofv3 counter runs (profiles/hbm_traffic.json), or None
+    if there is no measurement for this workload or the kernel source changed since it was taken."""
+    import hashlib
+    try:
+        rec = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json")))
+        src = os.path.join(ROOT, "paper_2508_08438_amd", "csrc", "skv_attn.hip")
+        if hashlib.sha256(open(src, "rb").read()).hexdigest() != rec["attn_source_sha256"]:
+            return None
+        t = rec["per_launch"][workload_key][kernel]
+        return t["read_bytes"] + t["write_bytes"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+def cpu_baseline(w, sess, mlen, pt, rows_target, flops_total, max_req=8):
+    """Time the oracle, as it stands, on the host cores: match over the whole batch, gather and fp64
+    attention on a bounded seeded sample (a few requests; a sample of their output rows), scaled to the
+    batch by algorithmic bytes / flops."""
     import numpy as np
+    import torch
     import oracle
+    from paper_2508_08438_amd.inputs import BLOCK
     threads = min(16, os.cpu_count() or 1)
     t0 = time.perf_counter()
     tree = oracle.OracleTree.from_workload(w)
@@ -41,33 +59,54 @@ def cpu_baseline(w, sess, mlen, pt, rows_target, flops_total):
     t0 = time.perf_counter()
     o_mlen, o_pt = tree.match(w.req_off, w.req_tokens, w.req_tenant, max(w.max_blocks, 1))
     t_match = time.perf_counter() - t0
-    kpool, vpool = sess.host_pools(o_pt)
-    t0 = time.perf_counter()
-    oracle.gather(kpool, vpool, o_mlen, o_pt)
-    t_gather = time.perf_counter() - t0
-    S = np.diff(w.req_off) - o_mlen
+    exact = bool(np.array_equal(o_mlen, mlen) and np.array_equal(o_pt, pt))
+    # sub-batch: a seeded choice of requests, their rows, and a compact pool of the pages they use
     g = np.random.default_rng(1234)
-    live = np.flatnonzero(S > 0)
-    rr = live[g.integers(0, len(live), rows_target)].astype(np.int32)
-    rp = (g.random(rows_target) * S[rr]).astype(np.int32)
-    rh = g.integers(0, w.attn.n_q_heads, rows_target).astype(np.int32)
+    S_all = np.diff(w.req_off) - o_mlen
+    live = np.flatnonzero(S_all > 0)
+    reqs = np.sort(g.choice(live, min(max_req, len(live)), replace=False))
+    S = S_all[reqs]
     q_off = np.concatenate([[0], np.cumsum(S)]).astype(np.int32)
-    q, kn, vn = (w.suffix_rows(x, o_mlen) for x in "qkv")
+    parts = {x: [] for x in "qkv"}
+    for r in reqs:
+        lo, hi = int(w.req_off[r]) + int(o_mlen[r]), int(w.req_off[r + 1])
+        for x in "qkv":
+            parts[x].append(w.token_rows(x, lo, hi))
+    q, kn, vn = (torch.cat(parts[x]) for x in "qkv")
+    sub_pt = o_pt[reqs]
+    pages = np.unique(sub_pt[sub_pt >= 0])
+    relabel = {int(p): i for i, p in enumerate(pages)}
+    cpt = np.array([[relabel.get(int(p), -1) for p in row] for row in sub_pt], dtype=np.int32).reshape(sub_pt.shape)
+    a = w.attn
+    shape = (max(len(pages), 1), BLOCK, a.n_kv_heads, a.head_dim)
+    kpool, vpool = torch.zeros(shape, dtype=a.torch_dtype), torch.zeros(shape, dtype=a.torch_dtype)
+    for i, pg in enumerate(pages):
+        kpool[i] = w.pool_pages("k", int(pg), int(pg) + 1)[0]
+        vpool[i] = w.pool_pages("v", int(pg), int(pg) + 1)[0]
     t0 = time.perf_counter()
-    want = oracle.attention(q, kn, vn, q_off, kpool, vpool, o_mlen, o_pt, scale=w.attn.scale,
+    oracle.gather(kpool, vpool, o_mlen[reqs], cpt)
+    t_gather = time.perf_counter() - t0
+    t_gather_full = t_gather * float(o_mlen.sum()) / max(float(o_mlen[reqs].sum()), 1.0)
+    rr = g.integers(0, len(reqs), rows_target).astype(np.int32)
+    rp = (g.random(rows_target) * S[rr]).astype(np.int32)
+    rh = g.integers(0, a.n_q_heads, rows_target).astype(np.int32)
+    t0 = time.perf_counter()
+    want = oracle.attention(q, kn, vn, q_off, kpool, vpool, o_mlen[reqs], cpt, scale=a.scale,
                             rows=(rr, rh, rp), n_threads=threads)
     t_attn = time.perf_counter() - t0
-    sample_flops = 4.0 * w.attn.head_dim * float((o_mlen[rr] + rp + 1).sum())
+    sample_flops = 4.0 * a.head_dim * float((o_mlen[reqs][rr] + rp + 1).sum())
     t_attn_full = t_attn * flops_total / sample_flops
     tokens = float(len(w.req_tokens))
-    got = sess.out.double().cpu().numpy()[q_off[rr] + rp, rh]
+    q_off_all = np.concatenate([[0], np.cumsum(S_all)]).astype(np.int64)
+    idx = torch.from_numpy(q_off_all[reqs[rr]] + rp).to(sess.out.device)
+    got = sess.out[idx, torch.from_numpy(rh.astype(np.int64)).to(idx.device)].double().cpu().numpy()
     err = float(np.abs(got - want).max())
-    exact = bool(np.array_equal(o_mlen, mlen) and np.array_equal(o_pt, pt))
-    return {"value": tokens / (t_match + t_gather + t_attn_full), "unit": "tokens/s", "cores": threads,
+    return {"value": tokens / (t_match + t_gather_full + t_attn_full), "unit": "tokens/s", "cores": threads,
             "kind": "oracle",
-            "sample": f"match+gather over all {w.n_req} requests ({t_match * 1e3:.2f} ms + {t_gather * 1e3:.2f} ms, "
-                      f"1 thread), fp64 attention on {rows_target} seeded (request, head, row) samples "
-                      f"({t_attn:.2f} s on {threads} threads) scaled to the batch by algorithmic flops",
+            "sample": f"match over all {w.n_req} requests ({t_match * 1e3:.2f} ms, 1 thread); gather of {len(reqs)} requests "
+                      f"({t_gather * 1e3:.2f} ms, 1 thread) and fp64 attention on {rows_target} seeded (request, head, row) "
+                      f"samples of those requests ({t_attn:.2f} s on {threads} threads), scaled to the batch by reused "
+                      f"bytes / algorithmic flops",
             "lookups_per_s": w.n_req / t_match, "tree_build_s": t_build}, err, exact
 
 
@@ -78,7 +117,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--hard", action="store_true", help="N(0,1) tensor entries instead of N(0,1)/sqrt(d)")
-    ap.add_argument("--cpu-rows", type=int, default=786432, help="oracle attention rows to time (0 = skip)")
+    ap.add_argument("--calib-mib", type=int, default=0,
+                    help="also run one plain streaming kernel (out = 2 * in over this many MiB of fp32) outside the "
+                         "timed region, as the known-size reference for HBM traffic counters")
+    ap.add_argument("--cpu-rows", type=int, default=262144, help="oracle attention rows to time (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures the path on ONE GPU; --gpus N with N > 1 is not supported "
@@ -98,6 +140,12 @@ def main():
     for _ in range(args.warmup):
         sess.step()
     torch.cuda.synchronize()
+    if args.calib_mib > 0:
+        src = torch.ones(args.calib_mib * (1 << 18), dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.mul(src, 2.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     K = args.steps
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
     t0 = time.perf_counter()
@@ -138,7 +186,9 @@ def main():
         "gather_gbs": gather_bytes / t_gather / 1e9 if mlen.sum() else 0.0,
         "roofline": {"bound": "mfma" if a.dtype == "bf16" else "alu", "kernel": "attn_bf16_kernel"
                      if a.dtype == "bf16" else "attn_f32_kernel", "achieved": achieved, "peak": peak,
-                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": None if args.hard else measured_traffic(args.workload, "attn_bf16_kernel"),
+                     "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled)",
                      "flops_per_launch": flops, "avg_launch_ms": t_attn * 1e3},
     }
     if args.cpu_rows > 0:

@@ -95,25 +95,50 @@ def test_match_configs_full_size(name):
             check_match(inputs.config4(literal=True), "c4_literal")
 
 
-def sample_rows(w, mlen, n, seed=0):
-    """(request, head, position) triples: always the first/last rows and the rows next to tile,
-    page and prefix boundaries, then uniform random ones."""
+def sample_rows(S, n_heads, n, seed=0):
+    """(request, head, position) triples over requests with suffix lengths S: always the first/last
+    rows and the rows next to tile, page and prefix boundaries, then uniform random ones."""
     g = np.random.default_rng(seed)
-    S = np.diff(w.req_off) - mlen
     rows = []
-    live = [r for r in range(w.n_req) if S[r] > 0]
+    live = [r for r in range(len(S)) if S[r] > 0]
     for r in live[: max(1, n // 64)]:
         for i in {0, 1, 15, 16, 31, 32, 63, 64, 65, 127, 128, S[r] - 2, S[r] - 1}:
             if 0 <= i < S[r]:
-                rows.append((r, int(g.integers(0, w.attn.n_q_heads)), int(i)))
+                rows.append((r, int(g.integers(0, n_heads)), int(i)))
     while len(rows) < n:
         r = live[int(g.integers(0, len(live)))]
-        rows.append((r, int(g.integers(0, w.attn.n_q_heads)), int(g.integers(0, S[r]))))
+        rows.append((r, int(g.integers(0, n_heads)), int(g.integers(0, S[r]))))
     a = np.array(rows[:n], dtype=np.int32)
     return a[:, 0].copy(), a[:, 1].copy(), a[:, 2].copy()
 
 
-def check_pipeline(w, label, n_sample=None, threads=16):
+def oracle_sub_batch(w, reqs, mlen, pt):
+    """Oracle inputs for a subset of requests: their Q/K_new/V_new rows and a compact pool holding only
+    the pages they reference (pages relabelled in order of first use; the oracle is invariant to that)."""
+    reqs = np.asarray(reqs)
+    S = (np.diff(w.req_off) - mlen)[reqs]
+    q_off = np.concatenate([[0], np.cumsum(S)]).astype(np.int32)
+    parts = {x: [] for x in "qkv"}
+    for r in reqs:
+        lo, hi = int(w.req_off[r]) + int(mlen[r]), int(w.req_off[r + 1])
+        for x in "qkv":
+            parts[x].append(w.token_rows(x, lo, hi))
+    q, kn, vn = (torch.cat(parts[x]) for x in "qkv")
+    sub_pt = pt[reqs]
+    pages = np.unique(sub_pt[sub_pt >= 0])
+    relabel = {int(p): i for i, p in enumerate(pages)}
+    cpt = np.vectorize(lambda p: relabel.get(int(p), -1))(sub_pt).astype(np.int32) if sub_pt.size else sub_pt
+    a = w.attn
+    shape = (max(len(pages), 1), B, a.n_kv_heads, a.head_dim)
+    kpool, vpool = torch.zeros(shape, dtype=a.torch_dtype), torch.zeros(shape, dtype=a.torch_dtype)
+    for i, pg in enumerate(pages):
+        kpool[i] = w.pool_pages("k", int(pg), int(pg) + 1)[0]
+        vpool[i] = w.pool_pages("v", int(pg), int(pg) + 1)[0]
+    return dict(q=q, knew=kn, vnew=vn, q_off=q_off, kpool=kpool, vpool=vpool, matched_len=mlen[reqs],
+                page_table=cpt, scale=a.scale), S
+
+
+def check_pipeline(w, label, n_sample=None, n_sub_req=None, threads=16):
     print(f"[pipeline] {label}", flush=True)
     s = _session(w)
     res = s.step()
@@ -122,30 +147,46 @@ def check_pipeline(w, label, n_sample=None, threads=16):
     mlen, pt = tree.match(w.req_off, w.req_tokens, w.req_tenant, max(w.max_blocks, 1))
     assert np.array_equal(res["matched_len"].cpu().numpy(), mlen)
     assert np.array_equal(res["page_table"].cpu().numpy(), pt)
-    kpool, vpool = s.host_pools(pt)
-    # gather: byte-exact
-    kc, vc = oracle.gather(kpool, vpool, mlen, pt)
-    n = kc.shape[0]
-    assert np.array_equal(res["ctx_off"].cpu().numpy(), np.concatenate([[0], np.cumsum(mlen)]))
+    g_hit, g_ucnt = s.counters()
+    hit, ucnt = tree.counters()
+    assert np.array_equal(g_hit, hit) and np.array_equal(g_ucnt, ucnt)
+    ctx_off = np.concatenate([[0], np.cumsum(mlen.astype(np.int64))])
+    assert np.array_equal(res["ctx_off"].cpu().numpy(), ctx_off)
+    q_off_all = np.concatenate([[0], np.cumsum(np.diff(w.req_off) - mlen)]).astype(np.int32)
+    assert np.array_equal(res["q_off"].cpu().numpy(), q_off_all)
     bits = torch.int32 if w.attn.dtype == "f32" else torch.int16
-    assert torch.equal(res["kctx"][:n].cpu().view(bits), kc.view(bits))
-    assert torch.equal(res["vctx"][:n].cpu().view(bits), vc.view(bits))
-    # attention
-    q_off = np.concatenate([[0], np.cumsum(np.diff(w.req_off) - mlen)]).astype(np.int32)
-    q, kn, vn = (w.suffix_rows(x, mlen) for x in "qkv")
-    got = res["out"].double().cpu().numpy()
-    if n_sample is None:
-        want = oracle.attention(q, kn, vn, q_off, kpool, vpool, mlen, pt, scale=w.attn.scale, n_threads=threads)
-        err = np.abs(got - want)
-        ref = np.abs(want).max()
+    # which requests the oracle recomputes: all of them, or a seeded subset that always holds the
+    # longest reuse and the longest suffix
+    if n_sub_req is None or n_sub_req >= w.n_req:
+        reqs = np.arange(w.n_req)
     else:
-        rows = sample_rows(w, mlen, n_sample)
-        want = oracle.attention(q, kn, vn, q_off, kpool, vpool, mlen, pt, scale=w.attn.scale, rows=rows,
-                                n_threads=threads)
-        pick = got[q_off[rows[0]] + rows[2], rows[1]]
-        err = np.abs(pick - want)
-        ref = np.abs(want).max()
-    print(f"   max-abs err {err.max():.3e}  (|ref| max {ref:.3e}, rel {err.max() / ref:.3e})", flush=True)
+        g = np.random.default_rng(7)
+        S_all = np.diff(w.req_off) - mlen
+        reqs = np.unique(np.concatenate([[int(np.argmax(mlen)), int(np.argmax(S_all))],
+                                         g.choice(w.n_req, n_sub_req, replace=False)]))
+    sub, S = oracle_sub_batch(w, reqs, mlen, pt)
+    # gather: byte-exact, request by request
+    kc, vc = oracle.gather(sub["kpool"], sub["vpool"], sub["matched_len"], sub["page_table"])
+    o = 0
+    for r in reqs:
+        n = int(mlen[r])
+        lo = int(ctx_off[r])
+        assert torch.equal(res["kctx"][lo: lo + n].cpu().view(bits), kc[o: o + n].view(bits)), (label, r)
+        assert torch.equal(res["vctx"][lo: lo + n].cpu().view(bits), vc[o: o + n].view(bits)), (label, r)
+        o += n
+    # attention
+    if n_sample is None:
+        want = oracle.attention(**sub, n_threads=threads)
+        got = torch.cat([res["out"][q_off_all[r]: q_off_all[r + 1]] for r in reqs]).double().cpu().numpy()
+    else:
+        rows = sample_rows(S, w.attn.n_q_heads, n_sample)
+        want = oracle.attention(**sub, rows=rows, n_threads=threads)
+        idx = torch.from_numpy(q_off_all[reqs[rows[0]]].astype(np.int64) + rows[2]).to(res["out"].device)
+        got = res["out"][idx, torch.from_numpy(rows[1].astype(np.int64)).to(idx.device)].double().cpu().numpy()
+    err = np.abs(got - want)
+    ref = np.abs(want).max()
+    print(f"   {len(reqs)} requests checked, max-abs err {err.max():.3e}  (|ref| max {ref:.3e}, rel {err.max() / ref:.3e})",
+          flush=True)
     assert err.max() <= TOL[w.attn.dtype], (label, err.max())
     return err.max(), ref
 
@@ -159,6 +200,20 @@ def test_pipeline_config2_bf16_sampled():
     check_pipeline(inputs.config2(), "c2", n_sample=4096)
     err, ref = check_pipeline(inputs.config2(hard=True), "c2_hard", n_sample=4096)
     assert err / ref < 2e-2  # N(0,1) inputs: the relative error has to be small too
+
+
+def test_pipeline_config3_streaming_mix():
+    check_pipeline(inputs.config3(), "c3", n_sample=4096, n_sub_req=24)
+    check_pipeline(inputs.config3(hard=True), "c3_hard", n_sample=2048, n_sub_req=12)
+
+
+def test_pipeline_config4_long_context():
+    check_pipeline(inputs.config4(), "c4", n_sample=1024, n_sub_req=4)
+    check_pipeline(inputs.config4(hard=True), "c4_hard", n_sample=512, n_sub_req=2)
+
+
+def test_pipeline_config5_sweep_quarter_sensitive():
+    check_pipeline(inputs.config5(0.25), "c5@0.25", n_sample=4096, n_sub_req=24)
 
 
 # ---- attention alone, on shapes the configs do not reach ---------------------------------------
