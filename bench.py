@@ -162,6 +162,19 @@ def main():
     ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev])
     t_match, t_gather, t_attn = (float(x) * 1e-3 for x in ms.mean(0))
 
+    # safeguard step (window roll + RDR scan), outside the timed region: a streaming pass over the block records
+    from paper_2508_08438_amd import binding as skv
+    pol = skv.rdr_policy(direction=0, tau=(1, 2), min_hits=2, n_consec=2)
+    sg = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    skv.skv_window_roll(sess.tree, pol)
+    sg[0].record()
+    for _ in range(10):
+        skv.skv_window_roll(sess.tree, pol)
+    sg[1].record()
+    torch.cuda.synchronize()
+    t_roll = sg[0].elapsed_time(sg[1]) * 1e-3 / 10
+    n_tree_blocks = sess.tree.info()["n_blocks"]
+
     tokens = float(len(w.req_tokens))
     pt = sess.page_table.cpu().numpy()
     flops = attention_flops(w, mlen)
@@ -184,6 +197,8 @@ def main():
         "computed_tokens_per_s": (tokens - float(mlen.sum())) / t_attn,
         "stage_ms": {"match": t_match * 1e3, "gather": t_gather * 1e3, "attention": t_attn * 1e3},
         "gather_gbs": gather_bytes / t_gather / 1e9 if mlen.sum() else 0.0,
+        "safeguard": {"blocks": n_tree_blocks, "ms": t_roll * 1e3, "gbs": n_tree_blocks * 68.0 / t_roll / 1e9,
+                      "bytes_per_block": 68},
         "roofline": {"bound": "mfma" if a.dtype == "bf16" else "alu", "kernel": "attn_bf16_kernel"
                      if a.dtype == "bf16" else "attn_f32_kernel", "achieved": achieved, "peak": peak,
                      "unit": "TFLOP/s", "frac": achieved / peak,

@@ -112,8 +112,38 @@ int skv_match(skv_tree* tree, int32_t n_req, const int32_t* d_req_off, const int
  * n_in_blocks entries; blocks that repeat an already cached block-prefix read 0. */
 int skv_counters_read(skv_tree* tree, uint32_t* d_hit, uint32_t* d_ucnt, void* stream);
 
-/* Start a new window: zero every block's hit counter and tenant set. */
+/* Clear the current window: zero every block's hit counter and tenant set (previous-window counters and
+ * the predicate streak are kept). */
 int skv_counters_reset(skv_tree* tree, void* stream);
+
+/* Safeguard policy (Section 4.2.2 and Section 6).  RDR = u_cnt / hit_cur is compared with
+ * tau = tau_num / tau_den as an exact rational (integers only).  direction 0: the predicate holds when
+ * RDR < tau (Section 6: probing lowers the RDR); direction 1: when RDR > tau and the previous window's
+ * distinct-tenant count u_pre <= u_pre_max (Section 4.2.2: narrow history, dispersed present).  Blocks
+ * with hit_cur == 0 or hit_cur < min_hits never meet it.  The paper fixes neither the direction nor the
+ * threshold, so both are the caller's. */
+typedef struct {
+  int32_t direction;   /* 0 or 1 */
+  uint32_t tau_num, tau_den; /* tau_den >= 1 */
+  uint32_t min_hits;
+  uint32_t n_consec;   /* >= 1: consecutive windows the predicate must hold before demotion */
+  uint32_t u_pre_max;  /* used by direction 1 only */
+} skv_rdr_policy;
+
+/* Safeguard step at a window boundary, over every cached block: evaluate the predicate on the current
+ * window's counters; a shareable block whose predicate has now held for n_consec consecutive windows is
+ * demoted to private (from then on only its creator_id matches it -- Section 6: after demotion, future
+ * cross-tenant hits on that block stop); then roll the window (hit_pre <- hit_cur, u_pre <- u_cnt, current
+ * counters and tenant set cleared).  If d_n_demoted is not NULL it receives the number of blocks demoted.
+ * Must not overlap with skv_match on the same tree.  Errors: SKV_EINVAL for null tree / policy,
+ * direction outside {0,1}, tau_den == 0 or n_consec == 0. */
+int skv_window_roll(skv_tree* tree, const skv_rdr_policy* policy, int32_t* d_n_demoted, void* stream);
+
+/* Per input block id: private_tag (0 shareable, 1 private, 255 for a block that repeats an already cached
+ * block-prefix) and the previous window's counters (Section 4.2.2: hit_pre, u_pre).  Arrays of n_in_blocks
+ * entries; any of them may be NULL. */
+int skv_block_state_read(skv_tree* tree, uint8_t* d_private, uint32_t* d_hit_pre, uint32_t* d_u_pre,
+                         void* stream);
 
 /* Device-side layout of the uncached suffixes: S_r = N_r - matched_len[r];
  * d_q_off[0] = 0, d_q_off[r+1] = d_q_off[r] + S_r  ([n_req+1], row offsets into Q/K_new/V_new/O). */

@@ -45,6 +45,9 @@ def lib():
         _lib.okv_counters.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         _lib.okv_sole_tenant.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
         _lib.okv_counters_reset.argtypes = [C.c_void_p]
+        _lib.okv_window_roll.restype = C.c_int64
+        _lib.okv_window_roll.argtypes = [C.c_void_p, C.c_int] + [C.c_uint32] * 5
+        _lib.okv_block_state.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.okv_gather.argtypes = [C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.okv_attention.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_int32] + \
@@ -120,6 +123,19 @@ class OracleTree:
         who = np.zeros(self.n_in_blocks, dtype=np.int32)
         self._l.okv_sole_tenant(self._t, self.n_in_blocks, _p(who))
         return who
+
+    def window_roll(self, direction=0, tau=(1, 2), min_hits=1, n_consec=1, u_pre_max=1):
+        """Safeguard step at a window boundary; returns the number of blocks demoted."""
+        return int(self._l.okv_window_roll(self._t, int(direction), int(tau[0]), int(tau[1]), int(min_hits),
+                                           int(n_consec), int(u_pre_max)))
+
+    def block_state(self):
+        """(private_tag, hit_pre, u_pre) per input block id; private_tag 255 = block created no entry."""
+        priv = np.zeros(self.n_in_blocks, dtype=np.uint8)
+        hp = np.zeros(self.n_in_blocks, dtype=np.uint32)
+        up = np.zeros(self.n_in_blocks, dtype=np.uint32)
+        self._l.okv_block_state(self._t, self.n_in_blocks, _p(priv), _p(hp), _p(up))
+        return priv, hp, up
 
     def reset_counters(self):
         self._l.okv_counters_reset(self._t)

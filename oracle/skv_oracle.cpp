@@ -21,6 +21,15 @@
 // key = whole first block, first insertion of a block-prefix wins, the creator's own hits
 // count) are listed in the design document.
 //
+//  * Safeguard step (Section 4.2.2 and Section 6): at the end of a monitoring window the RDR of each
+//    shareable block is tested against a threshold; a block that meets the predicate for enough
+//    consecutive windows is demoted to private (visible to its creator only), then the window rolls
+//    (hit_pre <- hit_cur, u_pre <- u_cnt, current counters cleared).  The paper states the trigger
+//    both ways (RDR above a threshold with a narrow history, Section 4.2.2; RDR below a threshold for
+//    consecutive windows, Section 6) and gives no threshold: the predicate is therefore a parameter,
+//    and which direction is "right" is parity unpinned.  The mechanics for a given parameter set are
+//    pinned against an independent recomputation from the counters.
+//
 // Pins: brute-force prefix scans, the 0 % / 100 % sensitive special cases, the visibility
 // invariants, counter conservation, and closed-form / library attention cases, all in the
 // CPU test-suite.  Unpinned: nothing in this file (the RDR *decision* is not implemented here).
@@ -49,6 +58,9 @@ struct BlockEntry {
   int64_t block_id;     // caller's index of the block that created this entry
   uint64_t hit_cur = 0;
   std::set<int32_t> tenants;  // distinct tenants that hit the block in the current window
+  uint64_t hit_pre = 0;       // previous window
+  uint64_t u_pre = 0;
+  uint32_t streak = 0;        // consecutive windows in which the RDR predicate held
 };
 
 struct Node {
@@ -290,6 +302,46 @@ void okv_sole_tenant(void* tp, int64_t n_in_blocks, int32_t* who) {
   for (int64_t i = 0; i < n_in_blocks; ++i) who[i] = -1;
   for_each_block(&((Tree*)tp)->root, [&](BlockEntry& e) {
     who[e.block_id] = e.tenants.empty() ? -1 : (e.tenants.size() == 1 ? *e.tenants.begin() : -2);
+  });
+}
+
+// Safeguard step at a window boundary.  direction 0: predicate = RDR < tau (Section 6); direction 1:
+// predicate = RDR > tau and u_pre <= u_pre_max (Section 4.2.2).  RDR = u_cnt / hit_cur is compared as
+// the exact rational: u_cnt * tau_den (<|>) tau_num * hit_cur.  Blocks with hit_cur < min_hits do not
+// meet the predicate.  A shareable block whose predicate has held for n_consec consecutive windows
+// (this one included) is demoted.  Returns the number of blocks demoted.
+int64_t okv_window_roll(void* tp, int direction, uint32_t tau_num, uint32_t tau_den, uint32_t min_hits,
+                        uint32_t n_consec, uint32_t u_pre_max) {
+  int64_t demoted = 0;
+  for_each_block(&((Tree*)tp)->root, [&](BlockEntry& e) {
+    const uint64_t u = e.tenants.size(), h = e.hit_cur;
+    bool pred = false;
+    if (h > 0 && h >= min_hits) {
+      if (direction == 0) pred = u * tau_den < (uint64_t)tau_num * h;
+      else pred = u * tau_den > (uint64_t)tau_num * h && e.u_pre <= u_pre_max;
+    }
+    e.streak = pred ? e.streak + 1 : 0;
+    if (!e.is_private && e.streak >= n_consec) {
+      e.is_private = true;   // creator_id is already recorded: from now on only the creator may reuse it
+      e.streak = 0;
+      ++demoted;
+    }
+    e.hit_pre = h;
+    e.u_pre = u;
+    e.hit_cur = 0;
+    e.tenants.clear();
+  });
+  return demoted;
+}
+
+// Per input block id: private_tag (0 / 1) of the entry it created, 255 for blocks that created none;
+// previous-window counters likewise (0 for blocks that created none).
+void okv_block_state(void* tp, int64_t n_in_blocks, uint8_t* is_private, uint32_t* hit_pre, uint32_t* u_pre) {
+  for (int64_t i = 0; i < n_in_blocks; ++i) { is_private[i] = 255; hit_pre[i] = 0; u_pre[i] = 0; }
+  for_each_block(&((Tree*)tp)->root, [&](BlockEntry& e) {
+    is_private[e.block_id] = e.is_private ? 1 : 0;
+    hit_pre[e.block_id] = (uint32_t)e.hit_pre;
+    u_pre[e.block_id] = (uint32_t)e.u_pre;
   });
 }
 

@@ -18,7 +18,7 @@ SKV_F32, SKV_BF16 = 0, 1
 
 EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_build",
            "skv_tree_info", "skv_tree_destroy", "skv_match", "skv_counters_read",
-           "skv_counters_reset", "skv_suffix_offsets", "skv_gather_kv",
+           "skv_counters_reset", "skv_window_roll", "skv_block_state_read", "skv_suffix_offsets", "skv_gather_kv",
            "skv_prefill_attn_workspace_size", "skv_prefill_attn"]
 
 
@@ -42,6 +42,11 @@ class AttnDesc(C.Structure):
                 ("dtype", C.c_int32), ("scale", C.c_float)]
 
 
+class RdrPolicy(C.Structure):
+    _fields_ = [("direction", C.c_int32), ("tau_num", C.c_uint32), ("tau_den", C.c_uint32),
+                ("min_hits", C.c_uint32), ("n_consec", C.c_uint32), ("u_pre_max", C.c_uint32)]
+
+
 _lib = None
 
 
@@ -63,6 +68,8 @@ def lib():
         l.skv_match.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, vp]
         l.skv_counters_read.argtypes = [vp, vp, vp, vp]
         l.skv_counters_reset.argtypes = [vp, vp]
+        l.skv_window_roll.argtypes = [vp, C.POINTER(RdrPolicy), vp, vp]
+        l.skv_block_state_read.argtypes = [vp, vp, vp, vp, vp]
         l.skv_suffix_offsets.argtypes = [i32, vp, vp, vp, vp]
         l.skv_gather_kv.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, i32, vp, vp, i32, vp, vp, vp, i64, vp]
         l.skv_prefill_attn_workspace_size.argtypes = [C.POINTER(AttnDesc), i32, i64, C.POINTER(C.c_size_t)]
@@ -162,6 +169,23 @@ def skv_counters_read(tree: Tree, hit, ucnt, stream=None):
 
 def skv_counters_reset(tree: Tree, stream=None):
     _check(lib().skv_counters_reset(tree.handle, _stream(stream)), "skv_counters_reset")
+
+
+def rdr_policy(direction=0, tau=(1, 2), min_hits=1, n_consec=1, u_pre_max=1) -> RdrPolicy:
+    return RdrPolicy(direction, tau[0], tau[1], min_hits, n_consec, u_pre_max)
+
+
+def skv_window_roll(tree: Tree, policy: RdrPolicy, n_demoted=None, stream=None):
+    assert n_demoted is None or (n_demoted.dtype == torch.int32 and n_demoted.numel() >= 1)
+    _check(lib().skv_window_roll(tree.handle, C.byref(policy), _dptr(n_demoted), _stream(stream)), "skv_window_roll")
+
+
+def skv_block_state_read(tree: Tree, private, hit_pre, u_pre, stream=None):
+    n = tree.info()["n_in_blocks"]
+    assert private is None or (private.dtype == torch.uint8 and private.numel() >= n)
+    assert all(x is None or (x.dtype == torch.int32 and x.numel() >= n) for x in (hit_pre, u_pre))
+    _check(lib().skv_block_state_read(tree.handle, _dptr(private), _dptr(hit_pre), _dptr(u_pre), _stream(stream)),
+           "skv_block_state_read")
 
 
 def skv_suffix_offsets(req_off, matched_len, q_off, stream=None):

@@ -25,12 +25,12 @@ struct SkvSlot {       // 16 bytes
   int32_t child;       // node index, -1 = empty
   int32_t pad;
 };
-#define SKV_CTR_STRIDE 8  // uint32 per block: [0] hit_cur, [1..4] tenant bitmap, [5..7] unused
+#define SKV_CTR_STRIDE 8  // uint32 per block: [0] hit_cur, [1..4] tenant bitmap, [5] hit_pre, [6] u_pre, [7] predicate streak
 
 struct SkvTreeDev {
   const int32_t* tok;     // [n_blocks][16]
   const int32_t* page;    // [n_blocks]   address vector
-  const int32_t* meta;    // [n_blocks]   bit31 = private_tag, bits 0..30 = creator_id
+  int32_t* meta;          // [n_blocks]   bit31 = private_tag, bits 0..30 = creator_id (demotion sets bit31)
   const int32_t* canon;   // [n_blocks]   input block id that created the entry
   uint32_t* ctr;          // [n_blocks][SKV_CTR_STRIDE]
   const SkvNode* nodes;   // [n_nodes+1]

@@ -85,6 +85,60 @@ __global__ void counters_scatter_kernel(SkvTreeDev t, uint32_t* hit, uint32_t* u
   }
 }
 
+__global__ void counters_clear_window_kernel(SkvTreeDev t) {
+  for (int b = blockIdx.x * blockDim.x + threadIdx.x; b < t.n_blocks; b += gridDim.x * blockDim.x) {
+    uint32_t* c = t.ctr + (size_t)b * SKV_CTR_STRIDE;
+    c[0] = 0; c[1] = 0; c[2] = 0; c[3] = 0; c[4] = 0;
+  }
+}
+
+// Safeguard step (SafeKV Section 4.2.2, Section 6): one thread per block; a streaming pass over the
+// counter records (32 B read + 32 B written per block) and the metadata word.
+__global__ void window_roll_kernel(SkvTreeDev t, skv_rdr_policy pol, int32_t* n_demoted) {
+  for (int b0 = blockIdx.x * blockDim.x; b0 < t.n_blocks; b0 += gridDim.x * blockDim.x) {
+    const int b = b0 + threadIdx.x;
+    bool demote = false;
+    if (b < t.n_blocks) {
+      uint4* rec = (uint4*)(t.ctr + (size_t)b * SKV_CTR_STRIDE);
+      const uint4 lo = rec[0], hi = rec[1];  // {hit, bm0, bm1, bm2}, {bm3, hit_pre, u_pre, streak}
+      const uint32_t h = lo.x;
+      const uint32_t u = __popc(lo.y) + __popc(lo.z) + __popc(lo.w) + __popc(hi.x);
+      bool pred = false;
+      if (h > 0 && h >= pol.min_hits) {
+        const unsigned long long lhs = (unsigned long long)u * pol.tau_den, rhs = (unsigned long long)pol.tau_num * h;
+        pred = pol.direction == 0 ? lhs < rhs : (lhs > rhs && hi.z <= pol.u_pre_max);
+      }
+      uint32_t streak = pred ? hi.w + 1 : 0;
+      const int m = t.meta[b];
+      if (m >= 0 && streak >= pol.n_consec) {  // shareable (bit 31 clear) and the predicate held long enough
+        t.meta[b] = m | (int)0x80000000;
+        streak = 0;
+        demote = true;
+      }
+      rec[0] = make_uint4(0u, 0u, 0u, 0u);
+      rec[1] = make_uint4(0u, h, u, streak);
+    }
+    if (n_demoted) {
+      const unsigned long long mask = __ballot(demote);
+      if (mask && (threadIdx.x & 63) == 0) atomicAdd(n_demoted, (int)__popcll(mask));
+    }
+  }
+}
+
+__global__ void block_state_scatter_kernel(SkvTreeDev t, uint8_t* priv, uint32_t* hit_pre, uint32_t* u_pre) {
+  for (int b = blockIdx.x * blockDim.x + threadIdx.x; b < t.n_blocks; b += gridDim.x * blockDim.x) {
+    const uint32_t* c = t.ctr + (size_t)b * SKV_CTR_STRIDE;
+    const int id = t.canon[b];
+    if (priv) priv[id] = t.meta[b] < 0 ? 1 : 0;
+    if (hit_pre) hit_pre[id] = c[5];
+    if (u_pre) u_pre[id] = c[6];
+  }
+}
+
+__global__ void fill_u8_kernel(uint8_t* p, size_t n, uint8_t v) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
 int grid_for(size_t n, int block) {
   size_t g = (n + block - 1) / block;
   if (g < 1) g = 1;
@@ -222,7 +276,7 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   char* base = (char*)d_slab;
   t->dev.tok = (const int32_t*)(base + L.tok);
   t->dev.page = (const int32_t*)(base + L.page);
-  t->dev.meta = (const int32_t*)(base + L.meta);
+  t->dev.meta = (int32_t*)(base + L.meta);
   t->dev.canon = (const int32_t*)(base + L.canon);
   t->dev.ctr = (uint32_t*)(base + L.ctr);
   t->dev.nodes = (const SkvNode*)(base + L.nodes);
@@ -275,8 +329,35 @@ extern "C" int skv_counters_read(skv_tree* t, uint32_t* d_hit, uint32_t* d_ucnt,
 
 extern "C" int skv_counters_reset(skv_tree* t, void* stream) {
   if (!t) return SKV_EINVAL;
-  size_t n = (size_t)t->dev.n_blocks * SKV_CTR_STRIDE;
-  if (n) fill_u32_kernel<<<grid_for(n, 256), 256, 0, (hipStream_t)stream>>>(t->dev.ctr, n, 0u);
+  if (t->dev.n_blocks)
+    counters_clear_window_kernel<<<grid_for((size_t)t->dev.n_blocks, 256), 256, 0, (hipStream_t)stream>>>(t->dev);
+  SKV_HIP(hipGetLastError());
+  return SKV_OK;
+}
+
+extern "C" int skv_window_roll(skv_tree* t, const skv_rdr_policy* pol, int32_t* d_n_demoted, void* stream) {
+  if (!t || !pol) return SKV_EINVAL;
+  if ((pol->direction != 0 && pol->direction != 1) || pol->tau_den == 0 || pol->n_consec == 0) return SKV_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  if (d_n_demoted) fill_u32_kernel<<<1, 64, 0, st>>>((uint32_t*)d_n_demoted, 1, 0u);
+  if (t->dev.n_blocks)
+    window_roll_kernel<<<grid_for((size_t)t->dev.n_blocks, 256), 256, 0, st>>>(t->dev, *pol, d_n_demoted);
+  SKV_HIP(hipGetLastError());
+  return SKV_OK;
+}
+
+extern "C" int skv_block_state_read(skv_tree* t, uint8_t* d_private, uint32_t* d_hit_pre, uint32_t* d_u_pre,
+                                    void* stream) {
+  if (!t) return SKV_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const size_t n = (size_t)t->n_in_blocks;
+  if (n) {
+    if (d_private) fill_u8_kernel<<<grid_for(n, 256), 256, 0, st>>>(d_private, n, (uint8_t)255);
+    if (d_hit_pre) fill_u32_kernel<<<grid_for(n, 256), 256, 0, st>>>(d_hit_pre, n, 0u);
+    if (d_u_pre) fill_u32_kernel<<<grid_for(n, 256), 256, 0, st>>>(d_u_pre, n, 0u);
+  }
+  if (t->dev.n_blocks)
+    block_state_scatter_kernel<<<grid_for((size_t)t->dev.n_blocks, 256), 256, 0, st>>>(t->dev, d_private, d_hit_pre, d_u_pre);
   SKV_HIP(hipGetLastError());
   return SKV_OK;
 }

@@ -109,3 +109,10 @@ def test_no_fallback_when_library_is_missing(skv, monkeypatch):
     monkeypatch.setattr(skv, "LIB_PATH", "/nonexistent/libskv.so")
     with pytest.raises(RuntimeError):
         skv.lib()
+
+
+def test_window_roll_argument_checks(skv):
+    l = skv.lib()
+    ok = skv.rdr_policy()
+    assert l.skv_window_roll(None, C.byref(ok), None, None) == -1
+    assert l.skv_block_state_read(None, None, None, None, None) == -1

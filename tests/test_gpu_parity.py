@@ -304,3 +304,60 @@ def test_error_codes_need_no_launch():
     desc = skv.attn_desc(8, 3, 128, torch.bfloat16)
     with pytest.raises(skv.SkvError):
         skv.skv_prefill_attn_workspace_size(desc, 1, 1)
+
+
+# ---- safeguard step: window roll + RDR predicate + demotion, several windows in a row ----------------
+POLICIES = [dict(direction=0, tau=(1, 2), min_hits=1, n_consec=1, u_pre_max=1),
+            dict(direction=0, tau=(2, 3), min_hits=3, n_consec=2, u_pre_max=1),
+            dict(direction=1, tau=(1, 3), min_hits=1, n_consec=1, u_pre_max=2)]
+
+
+def run_windows(w, label, policy, n_windows=4, seed=0):
+    skv = _skv()
+    print(f"[safeguard] {label} {policy}", flush=True)
+    s = _session(w, with_kv=False)
+    tree = oracle.OracleTree.from_workload(w)
+    pol = skv.rdr_policy(**policy)
+    n_dem = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    n = w.n_in_blocks
+    priv = torch.zeros(max(n, 1), dtype=torch.uint8, device="cuda:0")
+    hp = torch.zeros(max(n, 1), dtype=torch.int32, device="cuda:0")
+    up = torch.zeros(max(n, 1), dtype=torch.int32, device="cuda:0")
+    g = np.random.default_rng(seed)
+    total = 0
+    for win in range(n_windows):
+        tenants = g.integers(0, w.n_tenants, w.n_req).astype(np.int32)   # a new tenant mix every window
+        s.req_tenant.copy_(torch.from_numpy(tenants))
+        skv.skv_match(s.tree, s.req_off, s.req_tokens, s.req_tenant, s.max_blocks, s.matched_len, s.page_table)
+        mlen, pt = tree.match(w.req_off, w.req_tokens, tenants, s.max_blocks)
+        torch.cuda.synchronize()
+        assert np.array_equal(s.matched_len.cpu().numpy(), mlen), (label, win)   # demotions change visibility
+        assert np.array_equal(s.page_table.cpu().numpy(), pt), (label, win)
+        skv.skv_window_roll(s.tree, pol, n_dem)
+        want = tree.window_roll(**policy)
+        skv.skv_block_state_read(s.tree, priv, hp, up)
+        torch.cuda.synchronize()
+        o_priv, o_hp, o_up = tree.block_state()
+        assert int(n_dem.item()) == want, (label, win)
+        assert np.array_equal(priv[:n].cpu().numpy(), o_priv)
+        assert np.array_equal(hp[:n].cpu().numpy().view(np.uint32), o_hp)
+        assert np.array_equal(up[:n].cpu().numpy().view(np.uint32), o_up)
+        h, u = s.counters()
+        assert h.sum() == 0 and u.sum() == 0
+        total += want
+    return total
+
+
+def test_safeguard_small_cases_all_policies():
+    total = 0
+    for seed in range(40):
+        w = inputs.small_random(seed=seed, n_req=60, p_sens=0.3, n_tenants=3)
+        total += run_windows(w, f"small{seed}", POLICIES[seed % 3], seed=seed)
+    assert total > 50
+
+
+def test_safeguard_config3_and_config5():
+    assert run_windows(inputs.config3(), "c3", dict(direction=0, tau=(9, 10), min_hits=2, n_consec=1, u_pre_max=1),
+                       n_windows=3) > 0
+    run_windows(inputs.config5(0.25), "c5@0.25", POLICIES[1], n_windows=3)
+    run_windows(inputs.config2(), "c2", POLICIES[2], n_windows=3)
