@@ -46,7 +46,7 @@ struct AttnParams {
   const void *q, *knew, *vnew, *kpool, *vpool;
   void* out;
   const int32_t *q_off, *matched_len, *page_table;
-  const int32_t* items;      // int2 {request, q tile}
+  const int32_t* items;      // kItemInts ints per work item
   const int32_t* n_items;
   int n_req, max_blocks, n_pages, Hq, Hkv;
   int heads_per_wg;          // query heads of one kv head handled by one workgroup (1, 2 or 4)
@@ -54,8 +54,12 @@ struct AttnParams {
 };
 
 // ---- work list ---------------------------------------------------------------------------------
-// One workgroup.  items[] lists (request, q tile) pairs, a request's heaviest (last) tile first.
-__global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_off, int pos_per_wg,
+// One workgroup.  items[] lists one 32-byte record per (request, q tile) pair -- {request, q tile, first
+// row of the request, its suffix length S, its reused length L} -- so that a workgroup of the attention
+// kernel learns everything about its piece of work from one load.  A request's heaviest (last) tile first.
+constexpr int kItemInts = 8;
+__global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_off,
+                                     const int32_t* __restrict__ matched_len, int pos_per_wg,
                                      int max_items, int32_t* __restrict__ n_items, int32_t* __restrict__ items) {
   __shared__ int32_t sh[1024];
   __shared__ int32_t carry;
@@ -63,9 +67,11 @@ __global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_of
   __syncthreads();
   for (int base = 0; base < n_req; base += 1024) {
     const int r = base + threadIdx.x;
-    int nt = 0;
+    int nt = 0, S = 0, qb = 0, L = 0;
     if (r < n_req) {
-      const int S = q_off[r + 1] - q_off[r];
+      qb = q_off[r];
+      S = q_off[r + 1] - qb;
+      L = matched_len[r] > 0 ? matched_len[r] : 0;
       nt = S > 0 ? (S + pos_per_wg - 1) / pos_per_wg : 0;
     }
     sh[threadIdx.x] = nt;
@@ -79,8 +85,9 @@ __global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_of
     const int start = carry + sh[threadIdx.x] - nt;
     for (int k = 0; k < nt; ++k) {
       if (start + k < max_items) {
-        items[2 * (start + k)] = r;
-        items[2 * (start + k) + 1] = nt - 1 - k;
+        int4* rec = (int4*)(items + (size_t)kItemInts * (start + k));
+        rec[0] = make_int4(r, nt - 1 - k, qb, S);
+        rec[1] = make_int4(L, 0, 0, 0);
       }
     }
     __syncthreads();
@@ -115,6 +122,15 @@ __device__ inline RowSrc group_source(const AttnParams& p, int kvh, int L, int L
     s.n_valid = is_new ? min(16, Ltot - key0) : 0;
   }
   return s;
+}
+
+// Value of the lane 32 positions away (the other half of the wavefront): v_permlane32_swap exchanges the
+// upper half of its first operand with the lower half of its second.
+__device__ inline float swap_halves(float x) {
+  float a = x, b = x;
+  // the wait states the compiler places between a VALU write and this instruction are added by hand
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  return (threadIdx.x & 32) ? a : b;
 }
 
 struct Softmax {
@@ -155,12 +171,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
       item = rest / n_hg;
     }
   }
+  // the record is read together with the item count (the grid bound keeps the index inside the list)
+  const int4 rec0 = ((const int4*)(p.items + (size_t)kItemInts * item))[0];
+  const int L = __builtin_amdgcn_readfirstlane(p.items[(size_t)kItemInts * item + 4]);
   if (item >= *p.n_items) return;
-  const int r = p.items[2 * item];
-  const int qt = p.items[2 * item + 1];
-  const int qbase = p.q_off[r];
-  const int S = p.q_off[r + 1] - qbase;
-  const int L = p.matched_len[r] > 0 ? p.matched_len[r] : 0;
+  const int r = __builtin_amdgcn_readfirstlane(rec0.x);
+  const int qt = __builtin_amdgcn_readfirstlane(rec0.y);
+  const int qbase = __builtin_amdgcn_readfirstlane(rec0.z);
+  const int S = __builtin_amdgcn_readfirstlane(rec0.w);
   const int Ltot = L + S;
 
   const int head = kvh * G + hg * p.heads_per_wg + (wave % p.heads_per_wg);
@@ -294,12 +312,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   // 2^kRescaleLog2 (then O and the row sum are rescaled); otherwise exponentials are taken against
   // the stale reference, which leaves the normalised result unchanged.
   auto softmax = [&]() __attribute__((always_inline)) {
-    float mx = s[0][0];
+    float m4[4];   // four independent reduction chains
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int k = 0; k < 4; ++k) m4[k] = fmaxf(s[0][k], s[1][k]);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[mt][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    for (int e = 4; e < 16; ++e) m4[e & 3] = fmaxf(m4[e & 3], fmaxf(s[0][e], s[1][e]));
+    float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+    mx = fmaxf(mx, swap_halves(mx));
     if (__any(mx > sm.m_ref + thr)) {
       const float m_new = fmaxf(sm.m_ref, mx);
       const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((sm.m_ref - m_new) * c);
@@ -311,7 +330,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
         for (int e = 0; e < 16; ++e) o[a][e] *= alpha;
     }
     const float mc = sm.m_ref * c;
-    float sum = 0.f;
+    float sum4[4] = {0.f, 0.f, 0.f, 0.f};   // one partial row sum per 16-key group: independent chains
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -321,7 +340,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
         for (int e = 0; e < 8; e += 2) {
           const float e0 = __builtin_amdgcn_exp2f(s[mt][q2 * 8 + e] * c - mc);
           const float e1 = __builtin_amdgcn_exp2f(s[mt][q2 * 8 + e + 1] * c - mc);
-          sum += e0 + e1;
+          sum4[mt * 2 + q2] += e0 + e1;
           f32x2 pr = {e0, e1};
           bf16x2 cv = __builtin_convertvector(pr, bf16x2);
           pk[e] = cv[0];
@@ -329,7 +348,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
         }
         pb[mt * 2 + q2] = pk;
       }
-    sm.l_run += sum;
+    sm.l_run += (sum4[0] + sum4[1]) + (sum4[2] + sum4[3]);
   };
   // O^T += V^T P^T : [128 d][32 queries]
   auto pv_prefetch = [&](int kt) __attribute__((always_inline)) {
@@ -372,7 +391,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   // ---- normalise and store: lane holds query l32; d = 32 a + 8 (e/4) + 4 half + e%4
   if (pos0 >= S) return;
   {
-    const float lsum = sm.l_run + __shfl_xor(sm.l_run, 32);
+    const float lsum = sm.l_run + swap_halves(sm.l_run);
     const float inv = 1.0f / lsum;
     const int pos = pos0 + l32;
     if (pos < S) {
@@ -499,7 +518,7 @@ extern "C" int skv_prefill_attn_workspace_size(const skv_attn_desc* desc, int32_
   int rc = check_attn(desc);
   if (rc) return rc;
   if (n_req < 0 || total_q_rows < 0 || !bytes) return SKV_EINVAL;
-  *bytes = 256 + skv_align256((size_t)max_items_for(desc, n_req, total_q_rows) * 2 * sizeof(int32_t));
+  *bytes = 256 + skv_align256((size_t)max_items_for(desc, n_req, total_q_rows) * kItemInts * sizeof(int32_t));
   return SKV_OK;
 }
 
@@ -550,7 +569,7 @@ extern "C" int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const 
   const int n_hg = (desc->n_q_heads / desc->n_kv_heads) / p.heads_per_wg;
   const int64_t grid = max_items * desc->n_kv_heads * n_hg;
   if (grid > 0x7fffffff || max_items > 0x3fffffff) return SKV_ERANGE;
-  attn_schedule_kernel<<<1, 1024, 0, st>>>(n_req, d_q_off, pos_per_wg, (int)max_items,
+  attn_schedule_kernel<<<1, 1024, 0, st>>>(n_req, d_q_off, d_matched_len, pos_per_wg, (int)max_items,
                                            (int32_t*)d_workspace, (int32_t*)((char*)d_workspace + 256));
   SKV_HIP(hipGetLastError());
   attn_bf16_kernel<<<(int)grid, kThreads, 0, st>>>(p);
