@@ -175,6 +175,28 @@ def main():
     t_roll = sg[0].elapsed_time(sg[1]) * 1e-3 / 10
     n_tree_blocks = sess.tree.info()["n_blocks"]
 
+    # insert side, outside the timed region: the suffixes' full blocks written to fresh pages (read + write, K and V)
+    q_off_h = sess.q_off.cpu().numpy()
+    full = np.diff(q_off_h) // 16
+    n_new = int(full.sum())
+    t_scatter = None
+    if n_new:
+        mb = int(full.max())
+        table = np.full((w.n_req, mb), -1, np.int32)
+        table[np.arange(mb)[None, :] < full[:, None]] = np.random.default_rng(0).permutation(n_new).astype(np.int32)
+        table = torch.from_numpy(table).to(sess.device)
+        shape = (n_new, 16, w.attn.n_kv_heads, w.attn.head_dim)
+        kp2 = torch.empty(shape, dtype=w.attn.torch_dtype, device=sess.device)
+        vp2 = torch.empty_like(kp2)
+        skv.skv_scatter_kv(sess.desc, sess.knew, sess.vnew, sess.q_off, table, kp2, vp2)
+        sg[0].record()
+        for _ in range(10):
+            skv.skv_scatter_kv(sess.desc, sess.knew, sess.vnew, sess.q_off, table, kp2, vp2)
+        sg[1].record()
+        torch.cuda.synchronize()
+        t_scatter = sg[0].elapsed_time(sg[1]) * 1e-3 / 10
+        del kp2, vp2
+
     tokens = float(len(w.req_tokens))
     pt = sess.page_table.cpu().numpy()
     flops = attention_flops(w, mlen)
@@ -199,6 +221,10 @@ def main():
         "gather_gbs": gather_bytes / t_gather / 1e9 if mlen.sum() else 0.0,
         "safeguard": {"blocks": n_tree_blocks, "ms": t_roll * 1e3, "gbs": n_tree_blocks * 68.0 / t_roll / 1e9,
                       "bytes_per_block": 68},
+        "insert": None if t_scatter is None else {
+            "pages": n_new, "ms": t_scatter * 1e3,
+            "gbs": 2.0 * n_new * 16 * 2 * w.attn.n_kv_heads * w.attn.head_dim * (4 if w.attn.dtype == "f32" else 2)
+            / t_scatter / 1e9},
         "roofline": {"bound": "mfma" if a.dtype == "bf16" else "alu", "kernel": "attn_bf16_kernel"
                      if a.dtype == "bf16" else "attn_f32_kernel", "achieved": achieved, "peak": peak,
                      "unit": "TFLOP/s", "frac": achieved / peak,

@@ -139,6 +139,12 @@ typedef struct {
  * direction outside {0,1}, tau_den == 0 or n_consec == 0. */
 int skv_window_roll(skv_tree* tree, const skv_rdr_policy* policy, int32_t* d_n_demoted, void* stream);
 
+/* Promotion (Section 4.2.3: once background verification marks a block shareable, its visibility bit is
+ * flipped so that later lookups may reuse it across tenants): clears private_tag of the entries created by
+ * the n input block ids in d_block_ids (device, int32).  Ids outside [0, n_in_blocks) and ids of blocks
+ * that repeat an already cached block-prefix are ignored.  Must not overlap with skv_match on the tree. */
+int skv_promote(skv_tree* tree, const int32_t* d_block_ids, int32_t n, void* stream);
+
 /* Per input block id: private_tag (0 shareable, 1 private, 255 for a block that repeats an already cached
  * block-prefix) and the previous window's counters (Section 4.2.2: hit_pre, u_pre).  Arrays of n_in_blocks
  * entries; any of them may be NULL. */
@@ -170,6 +176,15 @@ int skv_gather_kv(const skv_attn_desc* desc, int32_t n_req, const void* d_kpool,
                   int32_t n_pages, const int32_t* d_matched_len, const int32_t* d_page_table,
                   int32_t max_blocks, int64_t* d_ctx_off, void* d_kctx, void* d_vctx,
                   int64_t ctx_capacity_tokens, void* stream);
+
+/* Insert side of the KV pool (Section 4.3.1 Insert: newly generated KV blocks are appended to the cache):
+ * the full 16-token blocks of request r's uncached suffix (rows d_q_off[r] + 16 j .. + 15 of d_knew / d_vnew)
+ * are written to pool page d_new_pages[r*max_new_blocks + j]; entries that are negative, outside
+ * [0, n_pages), or beyond the suffix's floor(S_r / 16) full blocks are skipped.  Byte-exact copy, the inverse
+ * of skv_gather_kv.  Two entries naming the same page race.  Errors as skv_gather_kv. */
+int skv_scatter_kv(const skv_attn_desc* desc, int32_t n_req, const void* d_knew, const void* d_vnew,
+                   const int32_t* d_q_off, const int32_t* d_new_pages, int32_t max_new_blocks, void* d_kpool,
+                   void* d_vpool, int32_t n_pages, void* stream);
 
 /* Bytes of device workspace skv_prefill_attn needs for n_req requests and at most
  * total_q_rows uncached tokens in the batch. */

@@ -48,6 +48,8 @@ def lib():
         _lib.okv_window_roll.restype = C.c_int64
         _lib.okv_window_roll.argtypes = [C.c_void_p, C.c_int] + [C.c_uint32] * 5
         _lib.okv_block_state.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.okv_promote.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
+        _lib.okv_scatter.argtypes = [C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32] + [C.c_void_p] * 4
         _lib.okv_gather.argtypes = [C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.okv_attention.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_int32] + \
@@ -129,6 +131,10 @@ class OracleTree:
         return int(self._l.okv_window_roll(self._t, int(direction), int(tau[0]), int(tau[1]), int(min_hits),
                                            int(n_consec), int(u_pre_max)))
 
+    def promote(self, block_ids):
+        ids = np.ascontiguousarray(block_ids, dtype=np.int64)
+        self._l.okv_promote(self._t, len(ids), _p(ids))
+
     def block_state(self):
         """(private_tag, hit_pre, u_pre) per input block id; private_tag 255 = block created no entry."""
         priv = np.zeros(self.n_in_blocks, dtype=np.uint8)
@@ -152,6 +158,15 @@ def gather(kpool: torch.Tensor, vpool: torch.Tensor, matched_len, page_table):
                      page_table.shape[1] if page_table.ndim == 2 else 0, _p(kpool), _p(vpool),
                      _p(kctx), _p(vctx))
     return kctx, vctx
+
+
+def scatter(knew: torch.Tensor, vnew: torch.Tensor, q_off, new_pages, kpool: torch.Tensor, vpool: torch.Tensor):
+    """Write the full blocks of every request's new K / V rows into the pool pages new_pages[r][j] (in place)."""
+    q_off, new_pages = _i32(q_off), _i32(new_pages)
+    row_bytes = knew[0].numel() * knew.element_size()
+    assert kpool[0].numel() * kpool.element_size() == row_bytes * BLOCK
+    lib().okv_scatter(row_bytes, len(q_off) - 1, _p(q_off), _p(new_pages), new_pages.shape[1], _p(knew.contiguous()),
+                      _p(vnew.contiguous()), _p(kpool), _p(vpool))
 
 
 def attention(q, knew, vnew, q_off, kpool, vpool, matched_len, page_table, scale=None, rows=None,

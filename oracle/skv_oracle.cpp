@@ -334,6 +334,33 @@ int64_t okv_window_roll(void* tp, int direction, uint32_t tau_num, uint32_t tau_
   return demoted;
 }
 
+// Promotion (Section 4.2.3: once a block is verified shareable its visibility bit is flipped): the
+// entries created by the listed input block ids become shareable.  Ids that created no entry are ignored.
+void okv_promote(void* tp, int64_t n, const int64_t* block_ids) {
+  std::set<int64_t> ids(block_ids, block_ids + n);
+  for_each_block(&((Tree*)tp)->root, [&](BlockEntry& e) {
+    if (ids.count(e.block_id)) e.is_private = false;
+  });
+}
+
+// Insert side of the KV pool (Section 4.3.1 Insert: newly generated KV blocks are appended): the full
+// 16-token blocks of request r's uncached suffix are written to the pages new_pages[r][j]; entries < 0
+// or beyond the suffix's full blocks are skipped.  row_bytes = bytes of one token row (all kv heads).
+void okv_scatter(int64_t row_bytes, int32_t n_req, const int32_t* q_off, const int32_t* new_pages,
+                 int32_t max_new_blocks, const void* knew, const void* vnew, void* kpool, void* vpool) {
+  const int64_t page_bytes = row_bytes * kBlock;
+  for (int32_t r = 0; r < n_req; ++r) {
+    const int32_t full = (q_off[r + 1] - q_off[r]) / kBlock;
+    for (int32_t j = 0; j < full && j < max_new_blocks; ++j) {
+      const int64_t p = new_pages[(int64_t)r * max_new_blocks + j];
+      if (p < 0) continue;
+      const int64_t src = ((int64_t)q_off[r] + (int64_t)j * kBlock) * row_bytes;
+      std::memcpy((char*)kpool + p * page_bytes, (const char*)knew + src, page_bytes);
+      std::memcpy((char*)vpool + p * page_bytes, (const char*)vnew + src, page_bytes);
+    }
+  }
+}
+
 // Per input block id: private_tag (0 / 1) of the entry it created, 255 for blocks that created none;
 // previous-window counters likewise (0 for blocks that created none).
 void okv_block_state(void* tp, int64_t n_in_blocks, uint8_t* is_private, uint32_t* hit_pre, uint32_t* u_pre) {

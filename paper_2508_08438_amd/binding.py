@@ -18,7 +18,8 @@ SKV_F32, SKV_BF16 = 0, 1
 
 EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_build",
            "skv_tree_info", "skv_tree_destroy", "skv_match", "skv_counters_read",
-           "skv_counters_reset", "skv_window_roll", "skv_block_state_read", "skv_suffix_offsets", "skv_gather_kv",
+           "skv_counters_reset", "skv_window_roll", "skv_promote", "skv_block_state_read", "skv_suffix_offsets", "skv_gather_kv",
+           "skv_scatter_kv",
            "skv_prefill_attn_workspace_size", "skv_prefill_attn"]
 
 
@@ -70,6 +71,8 @@ def lib():
         l.skv_counters_reset.argtypes = [vp, vp]
         l.skv_window_roll.argtypes = [vp, C.POINTER(RdrPolicy), vp, vp]
         l.skv_block_state_read.argtypes = [vp, vp, vp, vp, vp]
+        l.skv_promote.argtypes = [vp, vp, i32, vp]
+        l.skv_scatter_kv.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, vp, vp, i32, vp, vp, i32, vp]
         l.skv_suffix_offsets.argtypes = [i32, vp, vp, vp, vp]
         l.skv_gather_kv.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, i32, vp, vp, i32, vp, vp, vp, i64, vp]
         l.skv_prefill_attn_workspace_size.argtypes = [C.POINTER(AttnDesc), i32, i64, C.POINTER(C.c_size_t)]
@@ -178,6 +181,19 @@ def rdr_policy(direction=0, tau=(1, 2), min_hits=1, n_consec=1, u_pre_max=1) -> 
 def skv_window_roll(tree: Tree, policy: RdrPolicy, n_demoted=None, stream=None):
     assert n_demoted is None or (n_demoted.dtype == torch.int32 and n_demoted.numel() >= 1)
     _check(lib().skv_window_roll(tree.handle, C.byref(policy), _dptr(n_demoted), _stream(stream)), "skv_window_roll")
+
+
+def skv_promote(tree: Tree, block_ids, stream=None):
+    assert block_ids.dtype == torch.int32
+    _check(lib().skv_promote(tree.handle, _dptr(block_ids), block_ids.numel(), _stream(stream)), "skv_promote")
+
+
+def skv_scatter_kv(desc: AttnDesc, knew, vnew, q_off, new_pages, kpool, vpool, stream=None):
+    n_req = q_off.numel() - 1
+    assert new_pages.dtype == torch.int32 and new_pages.dim() == 2 and new_pages.shape[0] == n_req
+    _check(lib().skv_scatter_kv(C.byref(desc), n_req, _dptr(knew), _dptr(vnew), _dptr(q_off), _dptr(new_pages),
+                                new_pages.shape[1], _dptr(kpool), _dptr(vpool), kpool.shape[0], _stream(stream)),
+           "skv_scatter_kv")
 
 
 def skv_block_state_read(tree: Tree, private, hit_pre, u_pre, stream=None):

@@ -82,7 +82,66 @@ __global__ __launch_bounds__(kThreads) void gather_pages_kernel(
   }
 }
 
+// Inverse of the gather: one workgroup per (request, new block) slot of the table, persistent grid.
+__global__ __launch_bounds__(kThreads) void scatter_pages_kernel(
+    int n_req, const u32x4* __restrict__ knew, const u32x4* __restrict__ vnew, const int32_t* __restrict__ q_off,
+    const int32_t* __restrict__ new_pages, int max_new_blocks, u32x4* __restrict__ kpool, u32x4* __restrict__ vpool,
+    int n_pages, int page_vec) {
+  const int64_t slots = (int64_t)n_req * max_new_blocks;
+  for (int64_t sidx = blockIdx.x; sidx < slots; sidx += gridDim.x) {
+    const int r = (int)(sidx / max_new_blocks), j = (int)(sidx % max_new_blocks);
+    const int page = new_pages[sidx];
+    const int qb = q_off[r];
+    const int full = (q_off[r + 1] - qb) / SKV_BLOCK_TOKENS;
+    if (page < 0 || page >= n_pages || j >= full) continue;  // uniform per workgroup
+    const size_t src = ((size_t)qb + (size_t)j * SKV_BLOCK_TOKENS) * (page_vec / SKV_BLOCK_TOKENS);  // 16-byte vectors per row
+    const u32x4* ks = knew + src;
+    const u32x4* vs = vnew + src;
+    u32x4* kd = kpool + (size_t)page * page_vec;
+    u32x4* vd = vpool + (size_t)page * page_vec;
+    for (int base = 0; base < page_vec; base += kThreads * kUnroll) {
+      u32x4 a[kUnroll], b[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int i = base + u * kThreads + threadIdx.x;
+        if (i < page_vec) {
+          a[u] = __builtin_nontemporal_load(ks + i);
+          b[u] = __builtin_nontemporal_load(vs + i);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int i = base + u * kThreads + threadIdx.x;
+        if (i < page_vec) {
+          __builtin_nontemporal_store(a[u], kd + i);
+          __builtin_nontemporal_store(b[u], vd + i);
+        }
+      }
+    }
+  }
+}
+
 }  // namespace
+
+extern "C" int skv_scatter_kv(const skv_attn_desc* desc, int32_t n_req, const void* d_knew, const void* d_vnew,
+                              const int32_t* d_q_off, const int32_t* d_new_pages, int32_t max_new_blocks,
+                              void* d_kpool, void* d_vpool, int32_t n_pages, void* stream) {
+  if (!desc || n_req < 0 || n_pages < 0 || max_new_blocks < 0) return SKV_EINVAL;
+  if (desc->dtype != SKV_F32 && desc->dtype != SKV_BF16) return SKV_EINVAL;
+  if (desc->n_kv_heads < 1 || desc->head_dim < 1) return SKV_EINVAL;
+  const int64_t row_bytes = (int64_t)desc->n_kv_heads * desc->head_dim * (desc->dtype == SKV_F32 ? 4 : 2);
+  if (row_bytes % 16 || row_bytes * SKV_BLOCK_TOKENS / 16 > 0x7fffffff) return SKV_EINVAL;
+  if (n_req == 0 || max_new_blocks == 0) return SKV_OK;
+  if (!d_knew || !d_vnew || !d_q_off || !d_new_pages || !d_kpool || !d_vpool) return SKV_EINVAL;
+  if (((uintptr_t)d_kpool | (uintptr_t)d_vpool | (uintptr_t)d_knew | (uintptr_t)d_vnew) & 15) return SKV_EINVAL;
+  const int64_t slots = (int64_t)n_req * max_new_blocks;
+  const int grid = (int)(slots < 256 * 16 ? slots : 256 * 16);
+  scatter_pages_kernel<<<grid, kThreads, 0, (hipStream_t)stream>>>(
+      n_req, (const u32x4*)d_knew, (const u32x4*)d_vnew, d_q_off, d_new_pages, max_new_blocks, (u32x4*)d_kpool,
+      (u32x4*)d_vpool, n_pages, (int)(row_bytes * SKV_BLOCK_TOKENS / 16));
+  SKV_HIP(hipGetLastError());
+  return SKV_OK;
+}
 
 extern "C" int skv_gather_kv(const skv_attn_desc* desc, int32_t n_req, const void* d_kpool,
                              const void* d_vpool, int32_t n_pages, const int32_t* d_matched_len,

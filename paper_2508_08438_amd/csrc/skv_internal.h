@@ -32,6 +32,7 @@ struct SkvTreeDev {
   const int32_t* page;    // [n_blocks]   address vector
   int32_t* meta;          // [n_blocks]   bit31 = private_tag, bits 0..30 = creator_id (demotion sets bit31)
   const int32_t* canon;   // [n_blocks]   input block id that created the entry
+  const int32_t* flat_of; // [n_in_blocks] flat index of the entry an input block created, -1 if none
   uint32_t* ctr;          // [n_blocks][SKV_CTR_STRIDE]
   const SkvNode* nodes;   // [n_nodes+1]
   const SkvSlot* slots;

@@ -32,16 +32,17 @@ extern "C" const char* skv_strerror(int code) {
 namespace {
 
 struct Layout {  // byte offsets inside the slab
-  size_t tok, page, meta, canon, ctr, nodes, slots, total;
+  size_t tok, page, meta, canon, flat_of, ctr, nodes, slots, total;
 };
 
-Layout make_layout(size_t n_blocks, size_t n_nodes_incl_root, size_t n_slots) {
+Layout make_layout(size_t n_blocks, size_t n_in_blocks, size_t n_nodes_incl_root, size_t n_slots) {
   Layout l;
   size_t o = 0;
   l.tok = o;   o = skv_align256(o + n_blocks * 16 * sizeof(int32_t));
   l.page = o;  o = skv_align256(o + n_blocks * sizeof(int32_t));
   l.meta = o;  o = skv_align256(o + n_blocks * sizeof(int32_t));
   l.canon = o; o = skv_align256(o + n_blocks * sizeof(int32_t));
+  l.flat_of = o; o = skv_align256(o + (n_in_blocks ? n_in_blocks : 1) * sizeof(int32_t));
   l.nodes = o; o = skv_align256(o + n_nodes_incl_root * sizeof(SkvNode));
   l.slots = o; o = skv_align256(o + (n_slots ? n_slots : 1) * sizeof(SkvSlot));
   l.ctr = o;   o = skv_align256(o + n_blocks * SKV_CTR_STRIDE * sizeof(uint32_t));
@@ -135,6 +136,15 @@ __global__ void block_state_scatter_kernel(SkvTreeDev t, uint8_t* priv, uint32_t
   }
 }
 
+__global__ void promote_kernel(SkvTreeDev t, int64_t n_in_blocks, const int32_t* ids, int n) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const int id = ids[i];
+    if (id < 0 || id >= n_in_blocks) continue;
+    const int f = t.flat_of[id];
+    if (f >= 0) atomicAnd((unsigned int*)&t.meta[f], 0x7fffffffu);  // the visibility bit flips atomically
+  }
+}
+
 __global__ void fill_u8_kernel(uint8_t* p, size_t n, uint8_t v) {
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -153,7 +163,7 @@ extern "C" int skv_tree_build_size(const skv_tree_desc* desc, size_t* device_byt
   int rc = check_desc(desc, &nib);
   if (rc) return rc;
   if (!device_bytes) return SKV_EINVAL;
-  *device_bytes = make_layout((size_t)nib, (size_t)nib + 1, 4 * (size_t)nib + 4).total;
+  *device_bytes = make_layout((size_t)nib, (size_t)nib, (size_t)nib + 1, 4 * (size_t)nib + 4).total;
   return SKV_OK;
 }
 
@@ -254,19 +264,22 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   }
 
   // 4. stage and upload
-  const Layout L = make_layout((size_t)n_blocks, (size_t)n_nodes + 1, n_slots);
+  const Layout L = make_layout((size_t)n_blocks, (size_t)nib, (size_t)n_nodes + 1, n_slots);
   if (L.total > bytes) return SKV_ENOMEM;
   std::vector<char> host(L.ctr);  // everything before the counters
   int32_t* h_tok = (int32_t*)(host.data() + L.tok);
   int32_t* h_page = (int32_t*)(host.data() + L.page);
   int32_t* h_meta = (int32_t*)(host.data() + L.meta);
   int32_t* h_canon = (int32_t*)(host.data() + L.canon);
+  int32_t* h_flat_of = (int32_t*)(host.data() + L.flat_of);
+  for (int32_t b = 0; b < nib; ++b) h_flat_of[b] = -1;
   for (int32_t b = 0; b < n_blocks; ++b) {
     const int32_t f = flat[b], in = src[b];
     memcpy(h_tok + (size_t)f * 16, d->tokens + (size_t)in * 16, 64);
     h_page[f] = d->blk_page[in];
     h_meta[f] = (d->blk_sensitive[in] ? (int32_t)0x80000000 : 0) | d->blk_owner[in];
     h_canon[f] = in;
+    h_flat_of[in] = f;
   }
   memcpy(host.data() + L.nodes, nodes.data(), nodes.size() * sizeof(SkvNode));
   memcpy(host.data() + L.slots, slots.data(), slots.size() * sizeof(SkvSlot));
@@ -278,6 +291,7 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   t->dev.page = (const int32_t*)(base + L.page);
   t->dev.meta = (int32_t*)(base + L.meta);
   t->dev.canon = (const int32_t*)(base + L.canon);
+  t->dev.flat_of = (const int32_t*)(base + L.flat_of);
   t->dev.ctr = (uint32_t*)(base + L.ctr);
   t->dev.nodes = (const SkvNode*)(base + L.nodes);
   t->dev.slots = (const SkvSlot*)(base + L.slots);
@@ -342,6 +356,13 @@ extern "C" int skv_window_roll(skv_tree* t, const skv_rdr_policy* pol, int32_t* 
   if (d_n_demoted) fill_u32_kernel<<<1, 64, 0, st>>>((uint32_t*)d_n_demoted, 1, 0u);
   if (t->dev.n_blocks)
     window_roll_kernel<<<grid_for((size_t)t->dev.n_blocks, 256), 256, 0, st>>>(t->dev, *pol, d_n_demoted);
+  SKV_HIP(hipGetLastError());
+  return SKV_OK;
+}
+
+extern "C" int skv_promote(skv_tree* t, const int32_t* d_block_ids, int32_t n, void* stream) {
+  if (!t || n < 0 || (n > 0 && !d_block_ids)) return SKV_EINVAL;
+  if (n) promote_kernel<<<grid_for((size_t)n, 256), 256, 0, (hipStream_t)stream>>>(t->dev, t->n_in_blocks, d_block_ids, n);
   SKV_HIP(hipGetLastError());
   return SKV_OK;
 }

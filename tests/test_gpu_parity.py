@@ -361,3 +361,150 @@ def test_safeguard_config3_and_config5():
                        n_windows=3) > 0
     run_windows(inputs.config5(0.25), "c5@0.25", POLICIES[1], n_windows=3)
     run_windows(inputs.config2(), "c2", POLICIES[2], n_windows=3)
+
+
+# ---------------------------------------------------------------------------------------------
+# insert side: promotion (Section 4.2.3) and the write of new KV blocks into pool pages (Section 4.3.1)
+
+def check_promote(w, label, seed, frac=0.4):
+    skv = _skv()
+    print(f"[promote] {label}", flush=True)
+    s = _session(w, with_kv=False)
+    tree = oracle.OracleTree.from_workload(w)
+    g = np.random.default_rng(seed)
+    n = w.n_in_blocks
+    ids = np.flatnonzero(g.random(n) < frac).astype(np.int32)
+    ids_dev = np.concatenate([ids, [-1, n, n + 12345], ids[:3]]).astype(np.int32)   # invalid ids and repeats are ignored
+    skv.skv_promote(s.tree, torch.from_numpy(ids_dev).to("cuda:0"))
+    tree.promote(ids)
+    priv = torch.zeros(max(n, 1), dtype=torch.uint8, device="cuda:0")
+    hp = torch.zeros(max(n, 1), dtype=torch.int32, device="cuda:0")
+    up = torch.zeros(max(n, 1), dtype=torch.int32, device="cuda:0")
+    skv.skv_block_state_read(s.tree, priv, hp, up)
+    torch.cuda.synchronize()
+    assert np.array_equal(priv[:n].cpu().numpy(), tree.block_state()[0]), label
+    skv.skv_match(s.tree, s.req_off, s.req_tokens, s.req_tenant, s.max_blocks, s.matched_len, s.page_table)
+    mlen, pt = tree.match(w.req_off, w.req_tokens, w.req_tenant, s.max_blocks)
+    torch.cuda.synchronize()
+    assert np.array_equal(s.matched_len.cpu().numpy(), mlen), label
+    assert np.array_equal(s.page_table.cpu().numpy(), pt), label
+    hit, ucnt = s.counters()
+    o_hit, o_ucnt = tree.counters()
+    assert np.array_equal(hit, o_hit) and np.array_equal(ucnt, o_ucnt), label
+    return mlen
+
+
+def test_promote_small_cases_and_config5():
+    for seed in range(30):
+        check_promote(inputs.small_random(seed=seed, n_req=40, p_sens=0.6, n_tenants=4), f"small{seed}", seed)
+    w = inputs.config5(p_sensitive=0.75)
+    base, _ = oracle.OracleTree.from_workload(w).match(w.req_off, w.req_tokens, w.req_tenant, max(w.max_blocks, 1),
+                                                       update=False)
+    after = check_promote(w, "c5@0.75", 1, frac=0.5)
+    assert after.sum() > base.sum()                       # promotion does open up reuse at full size
+    skv = _skv()
+    s = _session(inputs.small_random(seed=1), with_kv=False)
+    skv.skv_promote(s.tree, torch.zeros(0, dtype=torch.int32, device="cuda:0"))   # empty list: no launch
+    torch.cuda.synchronize()
+
+
+def scatter_inputs(seed, R, H, d, dtype, max_s=200, p_alloc=0.85):
+    g = np.random.default_rng(seed)
+    S = g.integers(0, max_s, R)
+    S[:3] = [0, 15, 32]
+    q_off = np.concatenate([[0], np.cumsum(S)]).astype(np.int32)
+    T = int(q_off[-1])
+    knew = torch.from_numpy(g.standard_normal((T, H, d))).to(dtype)
+    vnew = torch.from_numpy(g.standard_normal((T, H, d))).to(dtype)
+    mb = int(max(S) // B) + 1
+    n_pages = R * mb + 5
+    perm = g.permutation(n_pages)
+    new_pages = np.full((R, mb), -1, np.int32)
+    alloc = g.random((R, mb)) < p_alloc
+    new_pages[alloc] = perm[: int(alloc.sum())]
+    kpool = torch.from_numpy(g.standard_normal((n_pages, B, H, d))).to(dtype)
+    vpool = torch.from_numpy(g.standard_normal((n_pages, B, H, d))).to(dtype)
+    return q_off, knew, vnew, new_pages, kpool, vpool
+
+
+def run_scatter(label, H, d, dtype, q_off, knew, vnew, new_pages, kpool, vpool):
+    skv = _skv()
+    print(f"[scatter] {label}", flush=True)
+    dev = "cuda:0"
+    desc = skv.attn_desc(H, H, d, "f32" if dtype == torch.float32 else "bf16", 1.0)
+    kp, vp = kpool.to(dev), vpool.to(dev)
+    skv.skv_scatter_kv(desc, knew.to(dev), vnew.to(dev), torch.from_numpy(q_off).to(dev),
+                       torch.from_numpy(new_pages).to(dev), kp, vp)
+    torch.cuda.synchronize()
+    oracle.scatter(knew, vnew, q_off, new_pages, kpool, vpool)          # in place on the host copies
+    assert torch.equal(kp.cpu().view(torch.uint8), kpool.view(torch.uint8)), label
+    assert torch.equal(vp.cpu().view(torch.uint8), vpool.view(torch.uint8)), label
+
+
+def test_scatter_small_ragged_cases():
+    for seed, (H, d, dtype) in enumerate([(2, 8, torch.float32), (8, 128, torch.bfloat16), (1, 64, torch.bfloat16),
+                                          (3, 40, torch.float32), (8, 64, torch.float32)]):
+        run_scatter(f"small{seed}", H, d, dtype, *scatter_inputs(seed, 9, H, d, dtype))
+    # out-of-range page ids are skipped like negative ones; an empty batch and a zero-column table launch nothing
+    q_off, knew, vnew, new_pages, kpool, vpool = scatter_inputs(7, 6, 2, 16, torch.float32)
+    bad = new_pages.copy()
+    sel = np.flatnonzero(new_pages.ravel() >= 0)[::3]
+    bad.ravel()[sel] = kpool.shape[0] + 3
+    ref = new_pages.copy()
+    ref.ravel()[sel] = -1
+    skv = _skv()
+    desc = skv.attn_desc(2, 2, 16, "f32", 1.0)
+    kp, vp = kpool.cuda(), vpool.cuda()
+    skv.skv_scatter_kv(desc, knew.cuda(), vnew.cuda(), torch.from_numpy(q_off).cuda(), torch.from_numpy(bad).cuda(), kp, vp)
+    torch.cuda.synchronize()
+    oracle.scatter(knew, vnew, q_off, ref, kpool, vpool)
+    assert torch.equal(kp.cpu(), kpool) and torch.equal(vp.cpu(), vpool)
+    skv.skv_scatter_kv(desc, knew.cuda(), vnew.cuda(), torch.zeros(1, dtype=torch.int32, device="cuda:0"),
+                       torch.zeros((0, 4), dtype=torch.int32, device="cuda:0"), kp, vp)
+    torch.cuda.synchronize()
+
+
+def test_scatter_then_gather_round_trip_config2():
+    """Full-size insert: every full block of config 2's uncached suffixes goes to a fresh page; the pages,
+    gathered back through the same table, are the suffix rows again, and match the oracle's pools."""
+    skv = _skv()
+    w = inputs.config2()
+    s = _session(w)
+    s.prepare()
+    s.match()
+    torch.cuda.synchronize()
+    q_off = s.q_off.cpu().numpy()
+    R = w.n_req
+    full = np.diff(q_off) // B
+    mb = int(full.max()) + 1
+    n_new = int(full.sum())
+    g = np.random.default_rng(0)
+    perm = g.permutation(n_new + 7).astype(np.int32)
+    new_pages = np.full((R, mb), -1, np.int32)
+    mask = np.arange(mb)[None, :] < full[:, None]
+    new_pages[mask] = perm[:n_new]
+    a = w.attn
+    shape = (n_new + 7, B, a.n_kv_heads, a.head_dim)
+    kp = torch.zeros(shape, dtype=a.torch_dtype, device="cuda:0")
+    vp = torch.zeros(shape, dtype=a.torch_dtype, device="cuda:0")
+    np_dev = torch.from_numpy(new_pages).cuda()
+    print(f"[scatter] c2 {n_new} pages", flush=True)
+    skv.skv_scatter_kv(s.desc, s.knew, s.vnew, s.q_off, np_dev, kp, vp)
+    torch.cuda.synchronize()
+    knew, vnew = s.knew.cpu(), s.vnew.cpu()                 # rows from the seeded generator
+    kpool, vpool = torch.zeros(shape, dtype=a.torch_dtype), torch.zeros(shape, dtype=a.torch_dtype)
+    oracle.scatter(knew, vnew, q_off, new_pages, kpool, vpool)
+    assert torch.equal(kp.cpu().view(torch.int16), kpool.view(torch.int16))
+    assert torch.equal(vp.cpu().view(torch.int16), vpool.view(torch.int16))
+    # round trip through the gather
+    full_len = torch.from_numpy((full * B).astype(np.int32)).cuda()
+    kctx = torch.zeros((n_new * B, a.n_kv_heads, a.head_dim), dtype=a.torch_dtype, device="cuda:0")
+    vctx = torch.zeros_like(kctx)
+    ctx_off = torch.zeros(R + 1, dtype=torch.int64, device="cuda:0")
+    skv.skv_gather_kv(s.desc, kp, vp, full_len, np_dev, mb, ctx_off, kctx, vctx)
+    torch.cuda.synchronize()
+    co = ctx_off.cpu().numpy()
+    for r in range(R):
+        n = int(full[r]) * B
+        assert torch.equal(kctx[co[r]: co[r] + n], s.knew[q_off[r]: q_off[r] + n])
+        assert torch.equal(vctx[co[r]: co[r] + n], s.vnew[q_off[r]: q_off[r] + n])
