@@ -48,6 +48,9 @@ def lib():
         _lib.okv_window_roll.restype = C.c_int64
         _lib.okv_window_roll.argtypes = [C.c_void_p, C.c_int] + [C.c_uint32] * 5
         _lib.okv_block_state.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.okv_insert_requests.restype = C.c_int64
+        _lib.okv_insert_requests.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 5 + [C.c_int32, C.c_int64,
+                                                                                        C.c_void_p, C.c_void_p]
         _lib.okv_promote.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
         _lib.okv_scatter.argtypes = [C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32] + [C.c_void_p] * 4
         _lib.okv_gather.argtypes = [C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
@@ -130,6 +133,20 @@ class OracleTree:
         """Safeguard step at a window boundary; returns the number of blocks demoted."""
         return int(self._l.okv_window_roll(self._t, int(direction), int(tau[0]), int(tau[1]), int(min_hits),
                                            int(n_consec), int(u_pre_max)))
+
+    def insert(self, req_off, req_tokens, req_tenant, matched_len, new_pages):
+        """Append the blocks the tree does not hold yet, private to the requesting tenant.  Returns
+        (first_inserted, n_inserted) per request; new entries take the ids n_in_blocks, n_in_blocks+1, ..."""
+        req_off, req_tokens, req_tenant = _i32(req_off), _i32(req_tokens), _i32(req_tenant)
+        matched_len, new_pages = _i32(matched_len), _i32(new_pages)
+        R = len(req_tenant)
+        assert new_pages.shape[0] == R
+        first = np.zeros(R, dtype=np.int32)
+        n = np.zeros(R, dtype=np.int32)
+        self.n_in_blocks = int(self._l.okv_insert_requests(
+            self._t, R, _p(req_off), _p(req_tokens), _p(req_tenant), _p(matched_len), _p(new_pages),
+            new_pages.shape[1], self.n_in_blocks, _p(first), _p(n)))
+        return first, n
 
     def promote(self, block_ids):
         ids = np.ascontiguousarray(block_ids, dtype=np.int64)

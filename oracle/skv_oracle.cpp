@@ -257,6 +257,57 @@ int okv_tree_insert(void* tp, int64_t n_seq, const int64_t* seq_off, const int32
   return 0;
 }
 
+// Blocks of a token sequence that already lie on a root path (tokens only; visibility plays no part).
+int64_t existing_prefix_blocks(Tree* t, const int32_t* tok, int64_t n_blocks) {
+  Node* node = &t->root;
+  int64_t j = 0;
+  while (j < n_blocks) {
+    auto it = node->children.find(key_at(tok + j * kBlock));
+    if (it == node->children.end()) return j;
+    Node* child = it->second.get();
+    for (size_t i = 0; i < child->blocks.size(); ++i) {
+      if (j == n_blocks || !(child->blocks[i].tokens == key_at(tok + j * kBlock))) return j;
+      ++j;
+    }
+    node = child;
+  }
+  return j;
+}
+
+// Insert after a prefill (Section 4.3.1 Insert; Section 4.2.1: every new block starts private): the full
+// blocks of request r that the tree does not hold yet are appended along its path with private_tag = 1 and
+// creator_id = the request's tenant.  One copy per block-prefix: blocks whose tokens are already on the path
+// keep their entry, whoever created it.  new_pages[r][j] is the page of the request's block
+// matched_len[r]/16 + j (the pages its suffix was written to); insertion stops at the first block without
+// a page (< 0 or beyond max_new_blocks).  New entries get the ids next_block_id, next_block_id+1, ... in
+// request order.  Per request: first_inserted = index of its first new block, n_inserted = how many.
+// Returns the next free block id.
+int64_t okv_insert_requests(void* tp, int32_t n_req, const int32_t* req_off, const int32_t* req_tokens,
+                            const int32_t* req_tenant, const int32_t* matched_len, const int32_t* new_pages,
+                            int32_t max_new_blocks, int64_t next_block_id, int32_t* first_inserted,
+                            int32_t* n_inserted) {
+  Tree* t = (Tree*)tp;
+  for (int32_t r = 0; r < n_req; ++r) {
+    const int32_t* tok = req_tokens + req_off[r];
+    int64_t nb = (req_off[r + 1] - req_off[r]) / kBlock;
+    const int64_t k_vis = matched_len[r] / kBlock;
+    int64_t have = 0;  // leading suffix blocks that come with a page
+    while (have < max_new_blocks && new_pages[(int64_t)r * max_new_blocks + have] >= 0) ++have;
+    if (nb > k_vis + have) nb = k_vis + have;
+    const int64_t k_exist = existing_prefix_blocks(t, tok, nb);
+    first_inserted[r] = (int32_t)k_exist;
+    n_inserted[r] = 0;
+    if (k_exist >= nb || k_exist < k_vis) continue;  // nothing new, or a matched length the tree cannot have given
+    std::vector<uint8_t> sens(nb, 1);
+    std::vector<int32_t> owner(nb, req_tenant[r]), page(nb, -1);
+    for (int64_t j = k_vis; j < nb; ++j) page[j] = new_pages[(int64_t)r * max_new_blocks + (j - k_vis)];
+    insert_sequence(t, tok, nb, sens.data(), owner.data(), page.data(), next_block_id - k_exist);
+    n_inserted[r] = (int32_t)(nb - k_exist);
+    next_block_id += nb - k_exist;
+  }
+  return next_block_id;
+}
+
 int64_t okv_tree_n_blocks(void* tp) { return ((Tree*)tp)->n_blocks; }
 int64_t okv_tree_n_nodes(void* tp) { return count_nodes(&((Tree*)tp)->root) - 1; }
 

@@ -130,3 +130,155 @@ def test_gather_of_scattered_pages_returns_the_rows():
     for r in range(R):
         assert torch.equal(kctx[ctx_off[r]: ctx_off[r + 1]], knew[q_off[r]: q_off[r] + full[r]])
         assert torch.equal(vctx[ctx_off[r]: ctx_off[r + 1]], vnew[q_off[r]: q_off[r] + full[r]])
+
+
+# ---------------------------------------------------------------------------------------------
+# Insert after prefill (Section 4.3.1 Insert, private by default): pinned against a dictionary keyed by
+# whole block-prefixes -- no tree, no compression, no splits -- that is updated by the same rule.
+
+def prefix_table(w):
+    table = {}
+    for s in range(len(w.seq_off) - 1):
+        lo, hi = int(w.seq_off[s]), int(w.seq_off[s + 1])
+        for j in range((hi - lo) // B):
+            key = w.seq_tokens[lo: lo + (j + 1) * B].tobytes()
+            if key not in table:
+                b = lo // B + j
+                table[key] = [bool(w.blk_sensitive[b]), int(w.blk_owner[b]), int(w.blk_page[b]), b]
+    return table
+
+
+def table_match(table, x, tenant):
+    pages, ids = [], []
+    for k in range(len(x) // B):
+        e = table.get(x[: (k + 1) * B].tobytes())
+        if e is None or (e[0] and e[1] != tenant):
+            break
+        pages.append(e[2])
+        ids.append(e[3])
+    return pages, ids
+
+
+def table_insert(table, x, tenant, k_vis, pages_row, next_id):
+    have = 0
+    while have < len(pages_row) and pages_row[have] >= 0:
+        have += 1
+    nb = min(len(x) // B, k_vis + have)
+    k_exist = 0
+    while k_exist < nb and x[: (k_exist + 1) * B].tobytes() in table:
+        k_exist += 1
+    if k_exist >= nb or k_exist < k_vis:
+        return k_exist, 0, next_id
+    for j in range(k_exist, nb):
+        table[x[: (j + 1) * B].tobytes()] = [True, tenant, int(pages_row[j - k_vis]), next_id]
+        next_id += 1
+    return k_exist, nb - k_exist, next_id
+
+
+def make_round(g, earlier, vocab, n_tenants, n_req, block_vocab):
+    """Requests that extend, cut or branch off earlier ones (or start afresh); ragged token tails included."""
+    reqs = []
+    for _ in range(n_req):
+        base = earlier[g.integers(len(earlier))] if earlier and g.random() < 0.8 else np.zeros(0, np.int32)
+        keep = int(g.integers(0, len(base) // B + 1)) * B
+        n_new = int(g.integers(0, 5))
+        if block_vocab:
+            tail = np.repeat(g.integers(0, block_vocab, n_new), B).astype(np.int32)
+        else:
+            tail = g.integers(0, vocab, n_new * B).astype(np.int32)
+        ragged = g.integers(0, vocab, int(g.integers(0, B))).astype(np.int32)
+        reqs.append(np.concatenate([base[:keep], tail, ragged]).astype(np.int32))
+    off = np.concatenate([[0], np.cumsum([len(x) for x in reqs])]).astype(np.int32)
+    toks = np.concatenate(reqs + [np.zeros(0, np.int32)]).astype(np.int32)
+    tenants = g.integers(0, n_tenants, n_req).astype(np.int32)
+    return reqs, off, toks, tenants
+
+
+def run_stream(seed, n_rounds=4, n_req=12, check=None):
+    """Several rounds of match -> insert on the oracle tree and on the dictionary; returns totals."""
+    block_vocab = 3 if seed % 3 == 0 else None
+    w = inputs.small_random(seed=seed, n_req=8, p_sens=0.4, n_tenants=3, block_vocab=block_vocab)
+    vocab = int(w.seq_tokens.max()) + 1 if len(w.seq_tokens) else 2
+    tree = OracleTree.from_workload(w)
+    table = prefix_table(w)
+    g = np.random.default_rng(1000 + seed)
+    next_page = w.n_pages
+    next_id = w.n_in_blocks
+    earlier = [w.req_tokens[w.req_off[r]: w.req_off[r + 1]] for r in range(w.n_req)]
+    totals = dict(inserted=0, splits_possible=0, blocked=0)
+    for rnd in range(n_rounds):
+        reqs, off, toks, tenants = make_round(g, earlier, vocab, w.n_tenants, n_req, block_vocab)
+        mb = max(max(len(x) // B for x in reqs), 1)
+        mlen, pt, ids = tree.match(off, toks, tenants, mb, want_ids=True)
+        for r, x in enumerate(reqs):                       # the dictionary agrees on the lookup
+            pages, bids = table_match(table, x, tenants[r])
+            assert mlen[r] == len(pages) * B and list(pt[r, : len(pages)]) == pages
+            assert list(ids[r, : len(pages)]) == bids
+        new_pages = np.full((n_req, mb + 1), -1, np.int32)
+        for r, x in enumerate(reqs):
+            n_suffix = len(x) // B - mlen[r] // B
+            if g.random() < 0.15:
+                n_suffix = int(g.integers(0, n_suffix + 1))   # some requests come with too few pages
+            new_pages[r, :n_suffix] = np.arange(next_page, next_page + n_suffix)
+            next_page += n_suffix
+        first, n = tree.insert(off, toks, tenants, mlen, new_pages)
+        for r, x in enumerate(reqs):
+            f, k, next_id = table_insert(table, x, int(tenants[r]), int(mlen[r]) // B, new_pages[r], next_id)
+            assert (first[r], n[r]) == (f, k), (seed, rnd, r)
+            totals["inserted"] += k
+            totals["blocked"] += int(f > mlen[r] // B)
+        assert tree.n_in_blocks == next_id
+        assert tree.n_blocks == len(table)
+        # every tenant, every request seen so far: the tree and the dictionary still agree
+        earlier += reqs
+        for t in range(w.n_tenants):
+            sample = [earlier[i] for i in g.choice(len(earlier), min(20, len(earlier)), replace=False)]
+            o = np.concatenate([[0], np.cumsum([len(x) for x in sample])]).astype(np.int32)
+            tk = np.concatenate(sample + [np.zeros(0, np.int32)]).astype(np.int32)
+            mb2 = max(max(len(x) // B for x in sample), 1)
+            ml2, pt2, id2 = tree.match(o, tk, np.full(len(sample), t, np.int32), mb2, update=False, want_ids=True)
+            for r, x in enumerate(sample):
+                pages, bids = table_match(table, x, t)
+                assert ml2[r] == len(pages) * B and list(pt2[r, : len(pages)]) == pages, (seed, rnd, t, r)
+                assert list(id2[r, : len(pages)]) == bids
+        if check:
+            check(tree, table, reqs, off, toks, tenants, new_pages, first, n)
+    return totals
+
+
+def test_insert_stream_matches_prefix_dictionary():
+    tot = dict(inserted=0, blocked=0)
+    for seed in range(60):
+        t = run_stream(seed)
+        tot["inserted"] += t["inserted"]
+        tot["blocked"] += t["blocked"]
+    assert tot["inserted"] > 1000 and tot["blocked"] > 20      # both the plain and the blocked case occur
+
+
+def test_inserted_blocks_are_private_until_promoted():
+    def check(tree, table, reqs, off, toks, tenants, new_pages, first, n):
+        mb = max(max(len(x) // B for x in reqs), 1)
+        same, _ = tree.match(off, toks, tenants, mb, update=False)
+        for r, x in enumerate(reqs):
+            if n[r] > 0:                                   # the requester now reuses everything it inserted
+                assert same[r] >= (first[r] + n[r]) * B or same[r] < first[r] * B
+        priv, _, _ = tree.block_state()
+        new_ids = np.arange(tree.n_in_blocks - int(n.sum()), tree.n_in_blocks)
+        assert np.all(priv[new_ids] == 1)
+    for seed in range(20):
+        run_stream(seed, check=check)
+    # promotion opens the inserted blocks to every tenant
+    w = inputs.small_random(seed=5, n_req=8, p_sens=0.0, n_tenants=3)
+    tree = OracleTree.from_workload(w)
+    g = np.random.default_rng(5)
+    x = g.integers(0, 1000, 4 * B).astype(np.int32)       # tokens no cached sequence has
+    off = np.array([0, len(x)], np.int32)
+    first, n = tree.insert(off, x, np.array([1], np.int32), np.array([0], np.int32),
+                           np.array([[900, 901, 902, 903]], np.int32))
+    assert (first[0], n[0]) == (0, 4)
+    for t, want in ((0, 0), (1, 4 * B), (2, 0)):
+        assert tree.match(off, x, np.array([t], np.int32), 4, update=False)[0][0] == want
+    tree.promote(np.arange(w.n_in_blocks, w.n_in_blocks + 4))
+    for t in range(3):
+        ml, pt = tree.match(off, x, np.array([t], np.int32), 4, update=False)
+        assert ml[0] == 4 * B and list(pt[0]) == [900, 901, 902, 903]
