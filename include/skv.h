@@ -72,11 +72,16 @@ typedef struct {
 /* Upper bound, in bytes, of the device slab skv_tree_build needs for this description. */
 int skv_tree_build_size(const skv_tree_desc* desc, size_t* device_bytes);
 
+/* Bytes of a slab that can hold block_capacity blocks (described plus later inserted ones, repeats
+ * included).  SKV_ERANGE beyond 2^26 - 1 blocks. */
+int skv_tree_size_for_capacity(int64_t block_capacity, size_t* device_bytes);
+
 /* Build the index (Section 4.3.1 Insert; Section 4.3.2 path compression): inserts the
  * sequences in order, where a block whose whole block-prefix is already cached keeps the
  * first insertion's metadata and page; collapses every non-branching run of blocks into one
  * node carrying a per-block page-id vector; writes the flattened tree into d_slab (256-byte
- * aligned, at least skv_tree_build_size bytes) and zeroes the counters.
+ * aligned, at least skv_tree_build_size bytes) and zeroes the counters.  A larger slab leaves room
+ * for skv_tree_insert: the capacity is the largest block count whose layout fits into `bytes`.
  * Errors: SKV_EINVAL for null pointers, block_tokens != 16, offsets that decrease or are not
  * multiples of 16, an owner outside [0, n_tenants), a page id outside [0, n_pages), the same
  * page id on two distinct cached blocks, or a misaligned slab; SKV_ERANGE for n_tenants
@@ -84,6 +89,29 @@ int skv_tree_build_size(const skv_tree_desc* desc, size_t* device_bytes);
  * Synchronises `stream` before returning. */
 int skv_tree_build(const skv_tree_desc* desc, void* d_slab, size_t bytes, void* stream,
                    skv_tree** out);
+
+/* Insert after a prefill (Section 4.3.1 Insert: new KV blocks are appended along the request's path;
+ * Section 4.2.1: every new block starts private, with the requester as creator_id).  All arrays are HOST
+ * arrays.  For request r (tokens req_tokens[req_off[r] .. req_off[r+1]), tenant req_tenant[r]) the full
+ * 16-token blocks that the tree does not hold yet are appended below the point where the request's token
+ * path leaves the tree (splitting a compressed node when that point lies inside it), private to the tenant.
+ * The index keeps one entry per block-prefix: blocks whose tokens are already on the path keep their entry,
+ * whoever created it, so a tenant that is blocked by another tenant's private block adds only what lies
+ * beyond the cached path.  new_pages[r*max_new_blocks + j] is the pool page of the request's block
+ * matched_len[r]/16 + j (the table skv_scatter_kv wrote through; matched_len as skv_match returned it);
+ * insertion stops at the first block without a page (< 0, or j >= max_new_blocks).  Requests are inserted
+ * in order, so a later request of the batch finds what an earlier one added.  New entries receive the input
+ * block ids n_in_blocks, n_in_blocks + 1, ... in that order, start with zeroed counters, and are visible to
+ * skv_match calls enqueued afterwards.  first_inserted[r] / n_inserted[r] report the index of the request's
+ * first new block and their number (pages given for blocks below first_inserted[r] stay unused).
+ * Errors, nothing changed: SKV_EINVAL for null pointers, decreasing offsets, a tenant outside
+ * [0, n_tenants), a page id outside [0, n_pages), already backing a cached block, or named twice;
+ * SKV_ENOMEM when the slab's capacity (blocks, or child-table slots) would be exceeded.
+ * Copies the changed records to the device on `stream` and synchronises it before returning.  Must not
+ * overlap with other calls on the tree. */
+int skv_tree_insert(skv_tree* tree, int32_t n_req, const int32_t* req_off, const int32_t* req_tokens,
+                    const int32_t* req_tenant, const int32_t* matched_len, const int32_t* new_pages,
+                    int32_t max_new_blocks, int32_t* first_inserted, int32_t* n_inserted, void* stream);
 
 /* n_nodes: compressed nodes (root excluded); n_blocks: distinct cached blocks;
  * n_in_blocks: blocks in the description (repeats included).  Any pointer may be NULL. */

@@ -15,8 +15,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libskv.so")
 BLOCK = 16
 SKV_F32, SKV_BF16 = 0, 1
+SKV_OK, SKV_EINVAL, SKV_ENOMEM, SKV_ERANGE, SKV_EHIP = 0, -1, -2, -3, -4
 
-EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_build",
+EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_size_for_capacity", "skv_tree_build", "skv_tree_insert",
            "skv_tree_info", "skv_tree_destroy", "skv_match", "skv_counters_read",
            "skv_counters_reset", "skv_window_roll", "skv_promote", "skv_block_state_read", "skv_suffix_offsets", "skv_gather_kv",
            "skv_scatter_kv",
@@ -72,6 +73,8 @@ def lib():
         l.skv_window_roll.argtypes = [vp, C.POINTER(RdrPolicy), vp, vp]
         l.skv_block_state_read.argtypes = [vp, vp, vp, vp, vp]
         l.skv_promote.argtypes = [vp, vp, i32, vp]
+        l.skv_tree_size_for_capacity.argtypes = [C.c_int64, C.POINTER(C.c_size_t)]
+        l.skv_tree_insert.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp]
         l.skv_scatter_kv.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, vp, vp, i32, vp, vp, i32, vp]
         l.skv_suffix_offsets.argtypes = [i32, vp, vp, vp, vp]
         l.skv_gather_kv.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, i32, vp, vp, i32, vp, vp, vp, i64, vp]
@@ -141,17 +144,40 @@ def skv_tree_build_size(seq_tokens, seq_off, blk_sensitive, blk_owner, blk_page,
     return n.value
 
 
+def skv_tree_size_for_capacity(block_capacity: int) -> int:
+    n = C.c_size_t()
+    _check(lib().skv_tree_size_for_capacity(block_capacity, C.byref(n)), "skv_tree_size_for_capacity")
+    return n.value
+
+
 def skv_tree_build(seq_tokens, seq_off, blk_sensitive, blk_owner, blk_page, n_tenants, n_pages,
-                   device="cuda", stream=None) -> Tree:
+                   device="cuda", stream=None, reserve_blocks=0) -> Tree:
+    """reserve_blocks: room, beyond the described blocks, for blocks inserted later."""
     d, _keep = _tree_desc(seq_tokens, seq_off, blk_sensitive, blk_owner, blk_page, n_tenants, n_pages)
     n = C.c_size_t()
     _check(lib().skv_tree_build_size(C.byref(d), C.byref(n)), "skv_tree_build_size")
+    if reserve_blocks:
+        _check(lib().skv_tree_size_for_capacity(len(_keep[4]) + reserve_blocks, C.byref(n)), "skv_tree_size_for_capacity")
     slab = torch.empty(n.value, dtype=torch.uint8, device=device)
     h = C.c_void_p()
     with torch.cuda.device(slab.device):
         _check(lib().skv_tree_build(C.byref(d), _dptr(slab), n.value, _stream(stream), C.byref(h)),
                "skv_tree_build")
     return Tree(h, slab)
+
+
+def skv_tree_insert(tree: Tree, req_off, req_tokens, req_tenant, matched_len, new_pages, stream=None):
+    """Host arrays in (numpy int32), per-request (first_inserted, n_inserted) out."""
+    a = [np.ascontiguousarray(x, dtype=np.int32) for x in (req_off, req_tokens, req_tenant, matched_len, new_pages)]
+    n_req = len(a[2])
+    assert len(a[0]) == n_req + 1 and len(a[3]) == n_req and a[4].ndim == 2 and a[4].shape[0] == n_req
+    first = np.zeros(n_req, dtype=np.int32)
+    n = np.zeros(n_req, dtype=np.int32)
+    hp = lambda x: C.c_void_p(x.ctypes.data) if x.size else None
+    with torch.cuda.device(tree.slab.device):
+        _check(lib().skv_tree_insert(tree.handle, n_req, hp(a[0]), hp(a[1]), hp(a[2]), hp(a[3]), hp(a[4]),
+                                     a[4].shape[1], hp(first), hp(n), _stream(stream)), "skv_tree_insert")
+    return first, n
 
 
 def skv_match(tree: Tree, req_off, req_tokens, req_tenant, max_blocks, matched_len, page_table, stream=None):

@@ -39,10 +39,12 @@ struct SkvTreeDev {
   int32_t n_blocks, n_nodes, n_tenants, n_pages;
 };
 
+struct SkvHostMirror;  // host copy of the structure, kept for insertions
 struct skv_tree {
   SkvTreeDev dev;
   int64_t n_in_blocks;
   int device;
+  SkvHostMirror* host;
 };
 
 // ---- block hash (host builds the tables, device probes them) -------------------------------

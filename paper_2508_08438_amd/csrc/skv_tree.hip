@@ -6,6 +6,7 @@
 // vector).  The tree is built without pointers: every distinct block-prefix gets an id
 // through one hash table keyed by (parent id, 16 tokens); non-branching runs are then laid
 // out contiguously and only branch points keep a child table.
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -31,9 +32,16 @@ extern "C" const char* skv_strerror(int code) {
 
 namespace {
 
+constexpr int64_t kMaxBlocks = 0x7fffffff / 32;
+
 struct Layout {  // byte offsets inside the slab
   size_t tok, page, meta, canon, flat_of, ctr, nodes, slots, total;
 };
+
+// Every array is sized for `cap` blocks: the entries the build creates plus room for later insertions.
+// A node holds at least one block, so cap + 1 node records always suffice; child tables are kept at most
+// half full and an outgrown table is left behind in the arena, which 8 slots per block cover.
+size_t slots_for(size_t cap) { return 8 * cap + 8; }
 
 Layout make_layout(size_t n_blocks, size_t n_in_blocks, size_t n_nodes_incl_root, size_t n_slots) {
   Layout l;
@@ -50,6 +58,24 @@ Layout make_layout(size_t n_blocks, size_t n_in_blocks, size_t n_nodes_incl_root
   return l;
 }
 
+}  // namespace
+
+// Host copy of the structure (not of the visibility bits or counters, which kernels change): what an
+// insertion has to read and extend.
+struct SkvHostMirror {
+  Layout L;
+  char* base = nullptr;               // the slab
+  int64_t cap_blocks = 0;
+  size_t slots_used = 0;
+  std::vector<SkvNode> nodes;         // [n_nodes + 1]
+  std::vector<int32_t> kids;          // children per node
+  std::vector<SkvSlot> slots;         // the arena up to slots_used
+  std::vector<int32_t> tok;           // [n_blocks][16], flat order
+  std::vector<uint8_t> page_used;     // [n_pages]
+};
+
+namespace {
+
 int check_desc(const skv_tree_desc* d, int64_t* n_in_blocks) {
   if (!d || !d->seq_off) return SKV_EINVAL;
   if (d->block_tokens != SKV_BLOCK_TOKENS) return SKV_EINVAL;
@@ -60,11 +86,13 @@ int check_desc(const skv_tree_desc* d, int64_t* n_in_blocks) {
     if (d->seq_off[s + 1] < d->seq_off[s] || d->seq_off[s + 1] % SKV_BLOCK_TOKENS) return SKV_EINVAL;
   }
   int64_t nib = d->seq_off[d->n_seq] / SKV_BLOCK_TOKENS;
-  if (nib > 0x7fffffff / 32) return SKV_ERANGE;
+  if (nib > kMaxBlocks) return SKV_ERANGE;
   if (nib > 0 && (!d->tokens || !d->blk_sensitive || !d->blk_owner || !d->blk_page)) return SKV_EINVAL;
   *n_in_blocks = nib;
   return SKV_OK;
 }
+
+Layout layout_for(size_t cap) { return make_layout(cap, cap, cap + 1, slots_for(cap)); }
 
 uint32_t next_pow2(uint32_t x) {
   uint32_t p = 1;
@@ -163,7 +191,14 @@ extern "C" int skv_tree_build_size(const skv_tree_desc* desc, size_t* device_byt
   int rc = check_desc(desc, &nib);
   if (rc) return rc;
   if (!device_bytes) return SKV_EINVAL;
-  *device_bytes = make_layout((size_t)nib, (size_t)nib, (size_t)nib + 1, 4 * (size_t)nib + 4).total;
+  *device_bytes = layout_for((size_t)nib).total;
+  return SKV_OK;
+}
+
+extern "C" int skv_tree_size_for_capacity(int64_t block_capacity, size_t* device_bytes) {
+  if (block_capacity < 0 || !device_bytes) return SKV_EINVAL;
+  if (block_capacity > kMaxBlocks) return SKV_ERANGE;
+  *device_bytes = layout_for((size_t)block_capacity).total;
   return SKV_OK;
 }
 
@@ -263,10 +298,16 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
     slots[pn.tab_off + s] = SkvSlot{(uint32_t)h, (uint32_t)(h >> 32), n, 0};
   }
 
-  // 4. stage and upload
-  const Layout L = make_layout((size_t)n_blocks, (size_t)nib, (size_t)n_nodes + 1, n_slots);
-  if (L.total > bytes) return SKV_ENOMEM;
-  std::vector<char> host(L.ctr);  // everything before the counters
+  // 4. stage and upload.  The slab's size fixes the capacity: the largest block count whose layout fits.
+  if (layout_for((size_t)nib).total > bytes) return SKV_ENOMEM;
+  int64_t cap_blocks = nib;
+  for (int64_t lo = nib, hi = kMaxBlocks; lo <= hi;) {
+    const int64_t mid = lo + (hi - lo) / 2;
+    if (layout_for((size_t)mid).total <= bytes) { cap_blocks = mid; lo = mid + 1; } else { hi = mid - 1; }
+  }
+  const Layout L = layout_for((size_t)cap_blocks);
+  if (n_slots > slots_for((size_t)cap_blocks)) return SKV_ENOMEM;
+  std::vector<char> host(L.slots + (n_slots ? n_slots : 1) * sizeof(SkvSlot));  // everything up to the used slots
   int32_t* h_tok = (int32_t*)(host.data() + L.tok);
   int32_t* h_page = (int32_t*)(host.data() + L.page);
   int32_t* h_meta = (int32_t*)(host.data() + L.meta);
@@ -287,6 +328,19 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   skv_tree* t = new (std::nothrow) skv_tree();
   if (!t) return SKV_EINVAL;
   char* base = (char*)d_slab;
+  SkvHostMirror* m = new (std::nothrow) SkvHostMirror();
+  if (!m) { delete t; return SKV_EINVAL; }
+  t->host = m;
+  m->L = L;
+  m->base = base;
+  m->cap_blocks = cap_blocks;
+  m->slots_used = n_slots;
+  m->nodes = nodes;
+  m->kids = kids;
+  m->slots.assign(slots.begin(), slots.begin() + n_slots);
+  m->tok.assign(h_tok, h_tok + (size_t)n_blocks * 16);
+  m->page_used.assign((size_t)d->n_pages, 0);
+  for (int32_t b = 0; b < n_blocks; ++b) m->page_used[h_page[b]] = 1;
   t->dev.tok = (const int32_t*)(base + L.tok);
   t->dev.page = (const int32_t*)(base + L.page);
   t->dev.meta = (int32_t*)(base + L.meta);
@@ -302,19 +356,211 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   t->n_in_blocks = nib;
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = hipGetDevice(&t->device);
-  if (e == hipSuccess && L.ctr) e = hipMemcpyAsync(base, host.data(), L.ctr, hipMemcpyHostToDevice, st);
-  if (e == hipSuccess && n_blocks) {
-    size_t n = (size_t)n_blocks * SKV_CTR_STRIDE;
+  if (e == hipSuccess) e = hipMemcpyAsync(base, host.data(), host.size(), hipMemcpyHostToDevice, st);
+  if (e == hipSuccess && cap_blocks) {  // counters of the whole capacity: inserted blocks start from zero
+    size_t n = (size_t)cap_blocks * SKV_CTR_STRIDE;
     fill_u32_kernel<<<grid_for(n, 256), 256, 0, st>>>(t->dev.ctr, n, 0u);
     e = hipGetLastError();
   }
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   if (e != hipSuccess) {
     skv_set_hip_error((int)e);
+    delete m;
     delete t;
     return SKV_EHIP;
   }
   *out = t;
+  return SKV_OK;
+}
+
+// ---- insertion after prefill (Section 4.3.1 Insert; Section 4.2.1: new blocks are private by default) ----
+namespace {
+
+struct Inserter {
+  skv_tree* t;
+  SkvHostMirror* m;
+  int64_t n_blocks, n_in;            // running totals
+  std::vector<int32_t> page, meta;   // per appended block
+  size_t node_lo, node_hi, slot_lo, slot_hi;  // dirty spans of records that existed before [lo, hi)
+  bool full = false;
+
+  void touch_node(size_t i) { node_lo = std::min(node_lo, i); node_hi = std::max(node_hi, i + 1); }
+  void touch_slot(size_t i) { slot_lo = std::min(slot_lo, i); slot_hi = std::max(slot_hi, i + 1); }
+
+  int32_t find_child(int32_t node, const int32_t* blk, uint64_t h) const {
+    const SkvNode& n = m->nodes[node];
+    if (!n.tab_cap) return -1;
+    for (uint32_t s = (uint32_t)h & (uint32_t)(n.tab_cap - 1);; s = (s + 1) & (uint32_t)(n.tab_cap - 1)) {
+      const SkvSlot& sl = m->slots[(size_t)n.tab_off + s];
+      if (sl.child < 0) return -1;
+      if (sl.hash_lo == (uint32_t)h && sl.hash_hi == (uint32_t)(h >> 32) &&
+          !memcmp(&m->tok[(size_t)m->nodes[sl.child].first * 16], blk, 64))
+        return sl.child;
+    }
+  }
+  void put(int32_t node, uint64_t h, int32_t child) {
+    const SkvNode& n = m->nodes[node];
+    uint32_t s = (uint32_t)h & (uint32_t)(n.tab_cap - 1);
+    while (m->slots[(size_t)n.tab_off + s].child >= 0) s = (s + 1) & (uint32_t)(n.tab_cap - 1);
+    m->slots[(size_t)n.tab_off + s] = SkvSlot{(uint32_t)h, (uint32_t)(h >> 32), child, 0};
+    touch_slot((size_t)n.tab_off + s);
+  }
+  // Adds a child; a table that would become more than half full moves to a fresh one of twice the size.
+  bool add_child(int32_t node, uint64_t h, int32_t child) {
+    SkvNode& n = m->nodes[node];
+    const int32_t kids = m->kids[node] + 1;
+    if (2 * kids > n.tab_cap) {
+      const int32_t cap = (int32_t)next_pow2((uint32_t)(2 * kids) < 4u ? 4u : (uint32_t)(2 * kids));
+      if (m->slots_used + (size_t)cap > slots_for((size_t)m->cap_blocks)) return false;
+      const SkvNode old = n;
+      n.tab_off = (int32_t)m->slots_used;
+      n.tab_cap = cap;
+      m->slots_used += (size_t)cap;
+      m->slots.resize(m->slots_used, SkvSlot{0, 0, -1, 0});
+      touch_slot((size_t)n.tab_off);
+      touch_slot(m->slots_used - 1);
+      for (int32_t i = 0; i < old.tab_cap; ++i) {
+        const SkvSlot sl = m->slots[(size_t)old.tab_off + i];
+        if (sl.child >= 0) put(node, ((uint64_t)sl.hash_hi << 32) | sl.hash_lo, sl.child);
+      }
+      touch_node((size_t)node);
+    }
+    put(node, h, child);
+    m->kids[node] = kids;
+    return true;
+  }
+  // One request: blocks [k_exist, nb) are appended as one node below the point where the path ends.
+  // Returns k_exist, or -1 when the slab is full.
+  int64_t insert(const int32_t* x, int64_t nb, int32_t tenant, const int32_t* pages, int64_t k_vis, int64_t* n_new) {
+    *n_new = 0;
+    int32_t node = 0;
+    int64_t i = 0;
+    while (i < nb) {
+      const uint64_t h = skv_hash_block_host(x + i * 16);
+      const int32_t c = find_child(node, x + i * 16, h);
+      if (c < 0) break;
+      const SkvNode run = m->nodes[c];
+      int64_t j = 1;
+      while (j < run.n_blocks && i + j < nb && !memcmp(&m->tok[((size_t)run.first + j) * 16], x + (i + j) * 16, 64)) ++j;
+      if (j < run.n_blocks) {
+        if (i + j == nb) return nb;  // the request ends inside the run: nothing new
+        if (i + j < k_vis) return i + j;  // caller's matched length is not one this tree gives
+        // split: the run keeps its first j blocks, a new node takes the rest together with the child table
+        if ((int64_t)m->nodes.size() + 2 > m->cap_blocks + 1) return -1;
+        const int32_t tail = (int32_t)m->nodes.size();
+        m->nodes.push_back(SkvNode{run.first + (int32_t)j, run.n_blocks - (int32_t)j, run.tab_off, run.tab_cap});
+        m->kids.push_back(m->kids[c]);
+        m->nodes[c].n_blocks = (int32_t)j;
+        m->nodes[c].tab_off = 0;
+        m->nodes[c].tab_cap = 0;
+        m->kids[c] = 0;
+        touch_node((size_t)c);
+        touch_node((size_t)tail);
+        if (!add_child(c, skv_hash_block_host(&m->tok[((size_t)run.first + j) * 16]), tail)) return -1;
+        node = c;
+        i += j;
+        break;
+      }
+      node = c;
+      i += j;
+    }
+    if (i >= nb || i < k_vis) return i;
+    const int64_t add = nb - i;
+    if (n_blocks + add > m->cap_blocks || n_in + add > m->cap_blocks) return -1;
+    const int32_t fresh = (int32_t)m->nodes.size();
+    m->nodes.push_back(SkvNode{(int32_t)n_blocks, (int32_t)add, 0, 0});
+    m->kids.push_back(0);
+    touch_node((size_t)fresh);
+    if (!add_child(node, skv_hash_block_host(x + i * 16), fresh)) return -1;
+    m->tok.insert(m->tok.end(), x + i * 16, x + nb * 16);
+    for (int64_t j = i; j < nb; ++j) {
+      page.push_back(pages[j - k_vis]);
+      meta.push_back((int32_t)0x80000000 | tenant);
+      m->page_used[pages[j - k_vis]] = 1;
+    }
+    n_blocks += add;
+    n_in += add;
+    *n_new = add;
+    return i;
+  }
+};
+
+}  // namespace
+
+extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_off, const int32_t* req_tokens,
+                               const int32_t* req_tenant, const int32_t* matched_len, const int32_t* new_pages,
+                               int32_t max_new_blocks, int32_t* first_inserted, int32_t* n_inserted, void* stream) {
+  if (!t || !t->host || n_req < 0 || max_new_blocks < 0) return SKV_EINVAL;
+  if (n_req == 0) return SKV_OK;
+  if (!req_off || !req_tenant || !matched_len || !first_inserted || !n_inserted) return SKV_EINVAL;
+  if (max_new_blocks > 0 && !new_pages) return SKV_EINVAL;
+  SkvHostMirror* m = t->host;
+  // validate everything before anything changes
+  std::vector<int32_t> have(n_req, 0);
+  {
+    std::vector<uint8_t> seen(m->page_used.size(), 0);
+    for (int32_t r = 0; r < n_req; ++r) {
+      if (req_off[r + 1] < req_off[r] || req_off[r] < 0 || matched_len[r] < 0) return SKV_EINVAL;
+      if (req_off[r + 1] > req_off[r] && !req_tokens) return SKV_EINVAL;
+      if (req_tenant[r] < 0 || req_tenant[r] >= t->dev.n_tenants) return SKV_EINVAL;
+      int32_t h = 0;
+      for (; h < max_new_blocks; ++h) {
+        const int32_t pg = new_pages[(size_t)r * max_new_blocks + h];
+        if (pg < 0) break;
+        if (pg >= t->dev.n_pages || m->page_used[pg] || seen[pg]) return SKV_EINVAL;
+        seen[pg] = 1;
+      }
+      have[r] = h;
+    }
+  }
+  // work on the mirror; a full slab restores the snapshot and changes nothing
+  const std::vector<SkvNode> nodes0 = m->nodes;
+  const std::vector<int32_t> kids0 = m->kids;
+  const std::vector<SkvSlot> slots0 = m->slots;
+  const std::vector<uint8_t> used0 = m->page_used;
+  const size_t slots_used0 = m->slots_used, tok0 = m->tok.size();
+  Inserter ins{t, m, t->dev.n_blocks, t->n_in_blocks, {}, {}, SIZE_MAX, 0, SIZE_MAX, 0};
+  bool full = false;
+  for (int32_t r = 0; r < n_req && !full; ++r) {
+    const int64_t k_vis = matched_len[r] / SKV_BLOCK_TOKENS;
+    int64_t nb = (req_off[r + 1] - req_off[r]) / SKV_BLOCK_TOKENS;
+    if (nb > k_vis + have[r]) nb = k_vis + have[r];
+    int64_t n_new = 0;
+    const int64_t first = ins.insert(req_tokens + req_off[r], nb, req_tenant[r],
+                                     new_pages + (size_t)r * max_new_blocks, k_vis, &n_new);
+    if (first < 0) { full = true; break; }
+    first_inserted[r] = (int32_t)first;
+    n_inserted[r] = (int32_t)n_new;
+  }
+  if (full) {
+    m->nodes = nodes0; m->kids = kids0; m->slots = slots0; m->page_used = used0;
+    m->slots_used = slots_used0; m->tok.resize(tok0);
+    return SKV_ENOMEM;
+  }
+  // upload: the appended block records, then the spans of node and slot records that changed
+  const int64_t nb0 = t->dev.n_blocks, nin0 = t->n_in_blocks, add = ins.n_blocks - nb0;
+  hipStream_t st = (hipStream_t)stream;
+  char* base = m->base;
+  if (add > 0) {
+    std::vector<int32_t> canon((size_t)add), flat_of((size_t)add);
+    for (int64_t i = 0; i < add; ++i) { canon[i] = (int32_t)(nin0 + i); flat_of[i] = (int32_t)(nb0 + i); }
+    SKV_HIP(hipMemcpyAsync(base + m->L.tok + (size_t)nb0 * 64, &m->tok[(size_t)nb0 * 16], (size_t)add * 64, hipMemcpyHostToDevice, st));
+    SKV_HIP(hipMemcpyAsync(base + m->L.page + (size_t)nb0 * 4, ins.page.data(), (size_t)add * 4, hipMemcpyHostToDevice, st));
+    SKV_HIP(hipMemcpyAsync(base + m->L.meta + (size_t)nb0 * 4, ins.meta.data(), (size_t)add * 4, hipMemcpyHostToDevice, st));
+    SKV_HIP(hipMemcpyAsync(base + m->L.canon + (size_t)nb0 * 4, canon.data(), (size_t)add * 4, hipMemcpyHostToDevice, st));
+    SKV_HIP(hipMemcpyAsync(base + m->L.flat_of + (size_t)nin0 * 4, flat_of.data(), (size_t)add * 4, hipMemcpyHostToDevice, st));
+    SKV_HIP(hipStreamSynchronize(st));  // the staging vectors die with this scope
+  }
+  if (ins.node_hi > ins.node_lo)
+    SKV_HIP(hipMemcpyAsync(base + m->L.nodes + ins.node_lo * sizeof(SkvNode), &m->nodes[ins.node_lo],
+                           (ins.node_hi - ins.node_lo) * sizeof(SkvNode), hipMemcpyHostToDevice, st));
+  if (ins.slot_hi > ins.slot_lo)
+    SKV_HIP(hipMemcpyAsync(base + m->L.slots + ins.slot_lo * sizeof(SkvSlot), &m->slots[ins.slot_lo],
+                           (ins.slot_hi - ins.slot_lo) * sizeof(SkvSlot), hipMemcpyHostToDevice, st));
+  SKV_HIP(hipStreamSynchronize(st));
+  t->dev.n_blocks = (int32_t)ins.n_blocks;
+  t->dev.n_nodes = (int32_t)m->nodes.size() - 1;
+  t->n_in_blocks = ins.n_in;
   return SKV_OK;
 }
 
@@ -326,7 +572,10 @@ extern "C" int skv_tree_info(const skv_tree* t, int64_t* n_nodes, int64_t* n_blo
   return SKV_OK;
 }
 
-extern "C" void skv_tree_destroy(skv_tree* t) { delete t; }
+extern "C" void skv_tree_destroy(skv_tree* t) {
+  if (t) delete t->host;
+  delete t;
+}
 
 extern "C" int skv_counters_read(skv_tree* t, uint32_t* d_hit, uint32_t* d_ucnt, void* stream) {
   if (!t || !d_hit || !d_ucnt) return SKV_EINVAL;

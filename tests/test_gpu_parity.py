@@ -508,3 +508,161 @@ def test_scatter_then_gather_round_trip_config2():
         n = int(full[r]) * B
         assert torch.equal(kctx[co[r]: co[r] + n], s.knew[q_off[r]: q_off[r] + n])
         assert torch.equal(vctx[co[r]: co[r] + n], s.vnew[q_off[r]: q_off[r] + n])
+
+
+# ---------------------------------------------------------------------------------------------
+# insert after prefill (Section 4.3.1 Insert): a stream of match -> insert rounds on the device tree and on
+# the oracle tree, which must stay interchangeable
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def device_match(skv, tree, off, toks, tenants, mb):
+    R = len(tenants)
+    mlen = torch.zeros(max(R, 1), dtype=torch.int32, device="cuda:0")
+    pt = torch.full((max(R, 1), mb), -1, dtype=torch.int32, device="cuda:0")
+    skv.skv_match(tree, _dev(off), _dev(toks) if len(toks) else torch.zeros(1, dtype=torch.int32, device="cuda:0"),
+                  _dev(tenants), mb, mlen, pt)
+    torch.cuda.synchronize()
+    return mlen[:R].cpu().numpy(), pt[:R].cpu().numpy()
+
+
+def compare_state(skv, dtree, otree, label):
+    n = otree.n_in_blocks
+    info = dtree.info()
+    # (node counts are not compared: how a chain is cut into nodes is not unique, only what lookups return is)
+    assert info["n_in_blocks"] == n and info["n_blocks"] == otree.n_blocks, label
+    hit = torch.zeros(max(n, 1), dtype=torch.int32, device="cuda:0")
+    ucnt = torch.zeros_like(hit)
+    priv = torch.zeros(max(n, 1), dtype=torch.uint8, device="cuda:0")
+    skv.skv_counters_read(dtree, hit, ucnt)
+    skv.skv_block_state_read(dtree, priv, torch.zeros_like(hit), torch.zeros_like(hit))
+    torch.cuda.synchronize()
+    o_hit, o_ucnt = otree.counters()
+    assert np.array_equal(hit[:n].cpu().numpy().view(np.uint32), o_hit), label
+    assert np.array_equal(ucnt[:n].cpu().numpy().view(np.uint32), o_ucnt), label
+    assert np.array_equal(priv[:n].cpu().numpy(), otree.block_state()[0]), label
+
+
+def run_insert_stream(seed, n_rounds=4, n_req=12):
+    from test_oracle_insert import make_round
+    skv = _skv()
+    block_vocab = 3 if seed % 3 == 0 else None
+    w = inputs.small_random(seed=seed, n_req=8, p_sens=0.4, n_tenants=3, block_vocab=block_vocab)
+    vocab = int(w.seq_tokens.max()) + 1 if len(w.seq_tokens) else 2
+    n_pages = w.n_pages + 4096
+    otree = oracle.OracleTree.from_workload(w)
+    dtree = skv.skv_tree_build(w.seq_tokens, w.seq_off, w.blk_sensitive, w.blk_owner, w.blk_page, w.n_tenants,
+                               n_pages, device="cuda:0", reserve_blocks=1024)
+    g = np.random.default_rng(1000 + seed)
+    next_page = w.n_pages
+    earlier = [w.req_tokens[w.req_off[r]: w.req_off[r + 1]] for r in range(w.n_req)]
+    inserted = 0
+    for rnd in range(n_rounds):
+        reqs, off, toks, tenants = make_round(g, earlier, vocab, w.n_tenants, n_req, block_vocab)
+        mb = max(max(len(x) // B for x in reqs), 1)
+        mlen, pt = device_match(skv, dtree, off, toks, tenants, mb)
+        o_mlen, o_pt = otree.match(off, toks, tenants, mb)
+        assert np.array_equal(mlen, o_mlen) and np.array_equal(pt, o_pt), (seed, rnd)
+        new_pages = np.full((n_req, mb + 1), -1, np.int32)
+        for r, x in enumerate(reqs):
+            n_suffix = len(x) // B - mlen[r] // B
+            if g.random() < 0.15:
+                n_suffix = int(g.integers(0, n_suffix + 1))
+            new_pages[r, :n_suffix] = np.arange(next_page, next_page + n_suffix)
+            next_page += n_suffix
+        first, n = skv.skv_tree_insert(dtree, off, toks, tenants, mlen, new_pages)
+        o_first, o_n = otree.insert(off, toks, tenants, mlen, new_pages)
+        assert np.array_equal(first, o_first) and np.array_equal(n, o_n), (seed, rnd)
+        inserted += int(n.sum())
+        if rnd == 1 and n.sum() > 0:    # the verifier clears some of the new blocks
+            ids = np.arange(otree.n_in_blocks - int(n.sum()), otree.n_in_blocks)[::2].astype(np.int32)
+            skv.skv_promote(dtree, _dev(ids))
+            otree.promote(ids)
+        earlier += reqs
+        # everything seen so far, as every tenant: lengths, page ids, then counters and visibility bits
+        for t in range(w.n_tenants):
+            sample = [earlier[i] for i in g.choice(len(earlier), min(24, len(earlier)), replace=False)]
+            o = np.concatenate([[0], np.cumsum([len(x) for x in sample])]).astype(np.int32)
+            tk = np.concatenate(sample + [np.zeros(0, np.int32)]).astype(np.int32)
+            ten = np.full(len(sample), t, np.int32)
+            mb2 = max(max(len(x) // B for x in sample), 1)
+            ml2, pt2 = device_match(skv, dtree, o, tk, ten, mb2)
+            o_ml2, o_pt2 = otree.match(o, tk, ten, mb2)
+            assert np.array_equal(ml2, o_ml2) and np.array_equal(pt2, o_pt2), (seed, rnd, t)
+        compare_state(skv, dtree, otree, (seed, rnd))
+    return inserted
+
+
+def test_insert_stream_small_cases():
+    total = 0
+    for seed in range(30):
+        print(f"[insert] stream {seed}", flush=True)
+        total += run_insert_stream(seed)
+    assert total > 500
+
+
+def test_insert_errors_leave_the_tree_unchanged():
+    skv = _skv()
+    w = inputs.small_random(seed=2, n_req=8, p_sens=0.3, n_tenants=3)
+    otree = oracle.OracleTree.from_workload(w)
+    dtree = skv.skv_tree_build(w.seq_tokens, w.seq_off, w.blk_sensitive, w.blk_owner, w.blk_page, w.n_tenants,
+                               w.n_pages + 64, device="cuda:0")          # no room reserved
+    g = np.random.default_rng(0)
+    x = g.integers(0, 1000, 40 * B).astype(np.int32)
+    off = np.array([0, len(x)], np.int32)
+    ten = np.array([1], np.int32)
+    pages = (w.n_pages + np.arange(40, dtype=np.int32))[None, :]
+    with pytest.raises(skv.SkvError) as e:
+        skv.skv_tree_insert(dtree, off, x, ten, np.zeros(1, np.int32), pages)
+    assert e.value.code == skv.SKV_ENOMEM
+    used = int(w.blk_page[0])
+    for bad_pages, bad_ten in ((np.array([[used]], np.int32), ten), (np.array([[w.n_pages + 64]], np.int32), ten),
+                               (np.array([[w.n_pages, w.n_pages]], np.int32), ten),
+                               (np.array([[w.n_pages]], np.int32), np.array([w.n_tenants], np.int32))):
+        with pytest.raises(skv.SkvError) as e:
+            skv.skv_tree_insert(dtree, off, x, bad_ten, np.zeros(1, np.int32), bad_pages)
+        assert e.value.code == skv.SKV_EINVAL
+    mb = max(w.max_blocks, 1)
+    mlen, pt = device_match(skv, dtree, w.req_off, w.req_tokens, w.req_tenant, mb)
+    o_mlen, o_pt = otree.match(w.req_off, w.req_tokens, w.req_tenant, mb)
+    assert np.array_equal(mlen, o_mlen) and np.array_equal(pt, o_pt)
+    compare_state(skv, dtree, otree, "after errors")
+
+
+@pytest.mark.parametrize("name", ["c2", "c3"])
+def test_insert_configs_full_size(name):
+    """Full size: every request of config 2 inserts its uncached suffix; asked again, requests reuse what
+    their own tenant inserted, and the oracle tree agrees block for block for the same and for other tenants."""
+    import time
+    skv = _skv()
+    w = inputs.CONFIGS[name]()
+    otree = oracle.OracleTree.from_workload(w)
+    nb_req = int((np.diff(w.req_off) // B).sum())
+    dtree = skv.skv_tree_build(w.seq_tokens, w.seq_off, w.blk_sensitive, w.blk_owner, w.blk_page, w.n_tenants,
+                               w.n_pages + nb_req, device="cuda:0", reserve_blocks=nb_req)
+    mb = max(w.max_blocks, 1)
+    mlen, pt = device_match(skv, dtree, w.req_off, w.req_tokens, w.req_tenant, mb)
+    o_mlen, o_pt = otree.match(w.req_off, w.req_tokens, w.req_tenant, mb)
+    assert np.array_equal(mlen, o_mlen) and np.array_equal(pt, o_pt)
+    full = np.diff(w.req_off) // B - mlen // B
+    new_pages = np.full((w.n_req, int(full.max())), -1, np.int32)
+    new_pages[np.arange(new_pages.shape[1])[None, :] < full[:, None]] = w.n_pages + np.arange(int(full.sum()), dtype=np.int32)
+    t0 = time.perf_counter()
+    first, n = skv.skv_tree_insert(dtree, w.req_off, w.req_tokens, w.req_tenant, mlen, new_pages)
+    dt = time.perf_counter() - t0
+    print(f"[insert] {name}: {int(n.sum())} of {int(full.sum())} suffix blocks new, {dt * 1e3:.2f} ms "
+          f"({w.n_req / dt:.0f} requests/s)", flush=True)
+    o_first, o_n = otree.insert(w.req_off, w.req_tokens, w.req_tenant, mlen, new_pages)
+    assert np.array_equal(first, o_first) and np.array_equal(n, o_n)
+    assert n.sum() > 0           # requests of one group share their prompt: only the first of them inserts it
+    for shift in (0, 1):
+        ten = ((w.req_tenant + shift) % w.n_tenants).astype(np.int32)
+        ml2, pt2 = device_match(skv, dtree, w.req_off, w.req_tokens, ten, mb)
+        o_ml2, o_pt2 = otree.match(w.req_off, w.req_tokens, ten, mb)
+        assert np.array_equal(ml2, o_ml2) and np.array_equal(pt2, o_pt2)
+        if shift == 0:
+            assert np.all(ml2 >= mlen)   # (many requests stop at other tenants' private blocks, before and after)
+            print(f"   reuse before {int(mlen.sum())} tokens, after {int(ml2.sum())}", flush=True)
+    compare_state(skv, dtree, otree, name)
