@@ -51,6 +51,10 @@ def lib():
         _lib.okv_insert_requests.restype = C.c_int64
         _lib.okv_insert_requests.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 5 + [C.c_int32, C.c_int64,
                                                                                         C.c_void_p, C.c_void_p]
+        _lib.okv_set_epoch.argtypes = [C.c_void_p, C.c_uint32]
+        _lib.okv_block_epochs.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
+        _lib.okv_evict.restype = C.c_int64
+        _lib.okv_evict.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.okv_promote.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
         _lib.okv_scatter.argtypes = [C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32] + [C.c_void_p] * 4
         _lib.okv_gather.argtypes = [C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
@@ -147,6 +151,23 @@ class OracleTree:
             self._t, R, _p(req_off), _p(req_tokens), _p(req_tenant), _p(matched_len), _p(new_pages),
             new_pages.shape[1], self.n_in_blocks, _p(first), _p(n)))
         return first, n
+
+    def set_epoch(self, epoch):
+        self._l.okv_set_epoch(self._t, int(epoch))
+
+    def epochs(self):
+        e = np.zeros(self.n_in_blocks, dtype=np.uint32)
+        self._l.okv_block_epochs(self._t, self.n_in_blocks, _p(e))
+        return e
+
+    def evict(self, n_want, protect_ids=()):
+        """Evict up to n_want blocks (oldest childless tails first).  Returns (block ids, pages) in order."""
+        prot = np.ascontiguousarray(protect_ids, dtype=np.int64)
+        n_want = int(min(n_want, self.n_blocks))
+        ids = np.zeros(max(n_want, 1), dtype=np.int64)
+        pages = np.zeros(max(n_want, 1), dtype=np.int32)
+        k = self._l.okv_evict(self._t, n_want, len(prot), _p(prot), _p(ids), _p(pages))
+        return ids[:k], pages[:k]
 
     def promote(self, block_ids):
         ids = np.ascontiguousarray(block_ids, dtype=np.int64)

@@ -61,6 +61,7 @@ struct BlockEntry {
   uint64_t hit_pre = 0;       // previous window
   uint64_t u_pre = 0;
   uint32_t streak = 0;        // consecutive windows in which the RDR predicate held
+  uint32_t epoch = 0;         // value of the global epoch counter at the entry's last access
 };
 
 struct Node {
@@ -72,6 +73,7 @@ struct Tree {
   Node root;  // holds no blocks
   int max_node_blocks;  // 0 = unlimited (path-compressed); 1 = one block per node
   int64_t n_blocks = 0;
+  uint32_t epoch = 0;   // global epoch counter (Section 4.3.2, progressive eviction)
 };
 
 BlockKey key_at(const int32_t* tok) {
@@ -112,6 +114,7 @@ void insert_sequence(Tree* t, const int32_t* tok, int64_t n_blocks, const uint8_
           e.creator_id = owner[j];
           e.page_id = page[j];
           e.block_id = first_block_id + j;
+          e.epoch = t->epoch;
           fresh->blocks.push_back(e);
           t->n_blocks++;
         }
@@ -308,6 +311,58 @@ int64_t okv_insert_requests(void* tp, int32_t n_req, const int32_t* req_off, con
   return next_block_id;
 }
 
+// Eviction (Section 4.3.1 Evict: epoch-based LRU, entries in use are protected; Section 4.3.2: space is
+// reclaimed from leaf to root, a compressed chain gives up the entries of its address vector one at a time
+// from its far end and disappears only when the vector is empty).  Only the last block of a childless node
+// can go without cutting off other entries; among those candidates that are not protected the one with the
+// oldest access epoch goes first (ties: the smaller block id), and the choice is repeated until n_want
+// blocks are gone or no candidate is left.  Writes the evicted block ids and their pages in eviction order.
+void okv_set_epoch(void* tp, uint32_t e) { ((Tree*)tp)->epoch = e; }
+
+void okv_block_epochs(void* tp, int64_t n_in_blocks, uint32_t* epoch) {
+  for (int64_t i = 0; i < n_in_blocks; ++i) epoch[i] = 0;
+  for_each_block(&((Tree*)tp)->root, [&](BlockEntry& e) { epoch[e.block_id] = e.epoch; });
+}
+
+struct Victim { Node* node = nullptr; Node* parent = nullptr; };
+void find_victim(Node* n, const std::set<int64_t>& prot, Victim* best) {
+  for (auto& kv : n->children) {
+    Node* c = kv.second.get();
+    if (c->children.empty() && !c->blocks.empty()) {
+      const BlockEntry& tail = c->blocks.back();
+      if (!prot.count(tail.block_id)) {
+        bool better = !best->node;
+        if (!better) {
+          const BlockEntry& b = best->node->blocks.back();
+          better = tail.epoch < b.epoch || (tail.epoch == b.epoch && tail.block_id < b.block_id);
+        }
+        if (better) { best->node = c; best->parent = n; }
+      }
+    }
+    find_victim(c, prot, best);
+  }
+}
+
+int64_t okv_evict(void* tp, int64_t n_want, int64_t n_protect, const int64_t* protect, int64_t* out_ids,
+                  int32_t* out_pages) {
+  Tree* t = (Tree*)tp;
+  std::set<int64_t> prot(protect, protect + n_protect);
+  int64_t done = 0;
+  while (done < n_want) {
+    Victim v;
+    find_victim(&t->root, prot, &v);
+    if (!v.node) break;
+    const BlockEntry gone = v.node->blocks.back();
+    out_ids[done] = gone.block_id;
+    out_pages[done] = gone.page_id;
+    ++done;
+    v.node->blocks.pop_back();
+    t->n_blocks--;
+    if (v.node->blocks.empty()) v.parent->children.erase(gone.tokens);  // it was the node's first block
+  }
+  return done;
+}
+
 int64_t okv_tree_n_blocks(void* tp) { return ((Tree*)tp)->n_blocks; }
 int64_t okv_tree_n_nodes(void* tp) { return count_nodes(&((Tree*)tp)->root) - 1; }
 
@@ -331,6 +386,7 @@ int okv_match(void* tp, int32_t n_req, const int32_t* req_off, const int32_t* re
       for (BlockEntry* e : hits) {
         e->hit_cur += 1;
         e->tenants.insert(req_tenant[r]);
+        e->epoch = t->epoch;
       }
   }
   return 0;
