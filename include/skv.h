@@ -113,7 +113,31 @@ int skv_tree_insert(skv_tree* tree, int32_t n_req, const int32_t* req_off, const
                     const int32_t* req_tenant, const int32_t* matched_len, const int32_t* new_pages,
                     int32_t max_new_blocks, int32_t* first_inserted, int32_t* n_inserted, void* stream);
 
-/* n_nodes: compressed nodes (root excluded); n_blocks: distinct cached blocks;
+/* Global epoch counter (Section 4.3.2: the index keeps a global epoch_counter and every entry its most
+ * recent access epoch).  skv_match calls enqueued after this call stamp `epoch` on every block they match;
+ * skv_tree_insert stamps it on the blocks it adds.  Blocks of the initial build start at epoch 0. */
+int skv_set_epoch(skv_tree* tree, uint32_t epoch);
+
+/* Last access epoch per input block id (device array of n_in_blocks entries; 0 for blocks without entry). */
+int skv_block_epochs_read(skv_tree* tree, uint32_t* d_epoch, void* stream);
+
+/* Eviction (Section 4.3.1 Evict: epoch-based LRU, entries in use are protected; Section 4.3.2 progressive
+ * eviction: space is reclaimed from leaf to root, and a compressed chain releases the entries of its
+ * address vector one by one from its far end, the node itself only when the vector is empty).  Only the
+ * last block of a childless node can be removed without cutting off other entries.  Among these candidates,
+ * skipping the ones whose input block id is listed in protect_ids (HOST array: blocks in use, e.g. those a
+ * running batch matched), the block with the oldest access epoch is removed first (ties: the smaller input
+ * block id); this repeats until n_want blocks are gone or no candidate is left.  evicted_ids / evicted_pages
+ * (HOST arrays of n_want entries) receive the removed blocks and their pool pages in removal order, so the
+ * caller can hand the pages out again; *n_evicted their number.  Removed blocks read as absent from then on
+ * (skv_counters_read and skv_block_state_read report them like blocks without entry); their record space in
+ * the slab is not reused.  Reads the epochs back from the device and uploads the changed records on
+ * `stream`, synchronising it; must not overlap with other calls on the tree.
+ * Errors: SKV_EINVAL for null pointers or negative counts. */
+int skv_evict(skv_tree* tree, int64_t n_want, const int32_t* protect_ids, int64_t n_protect,
+              int32_t* evicted_ids, int32_t* evicted_pages, int64_t* n_evicted, void* stream);
+
+/* n_nodes: compressed nodes (root excluded); n_blocks: distinct cached blocks (evicted ones not counted);
  * n_in_blocks: blocks in the description (repeats included).  Any pointer may be NULL. */
 int skv_tree_info(const skv_tree* tree, int64_t* n_nodes, int64_t* n_blocks, int64_t* n_in_blocks);
 

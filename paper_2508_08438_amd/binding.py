@@ -17,7 +17,7 @@ BLOCK = 16
 SKV_F32, SKV_BF16 = 0, 1
 SKV_OK, SKV_EINVAL, SKV_ENOMEM, SKV_ERANGE, SKV_EHIP = 0, -1, -2, -3, -4
 
-EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_size_for_capacity", "skv_tree_build", "skv_tree_insert",
+EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_size_for_capacity", "skv_tree_build", "skv_tree_insert", "skv_set_epoch", "skv_block_epochs_read", "skv_evict",
            "skv_tree_info", "skv_tree_destroy", "skv_match", "skv_counters_read",
            "skv_counters_reset", "skv_window_roll", "skv_promote", "skv_block_state_read", "skv_suffix_offsets", "skv_gather_kv",
            "skv_scatter_kv",
@@ -73,6 +73,9 @@ def lib():
         l.skv_window_roll.argtypes = [vp, C.POINTER(RdrPolicy), vp, vp]
         l.skv_block_state_read.argtypes = [vp, vp, vp, vp, vp]
         l.skv_promote.argtypes = [vp, vp, i32, vp]
+        l.skv_set_epoch.argtypes = [vp, C.c_uint32]
+        l.skv_block_epochs_read.argtypes = [vp, vp, vp]
+        l.skv_evict.argtypes = [vp, C.c_int64, vp, C.c_int64, vp, vp, C.POINTER(C.c_int64), vp]
         l.skv_tree_size_for_capacity.argtypes = [C.c_int64, C.POINTER(C.c_size_t)]
         l.skv_tree_insert.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp]
         l.skv_scatter_kv.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, vp, vp, i32, vp, vp, i32, vp]
@@ -178,6 +181,28 @@ def skv_tree_insert(tree: Tree, req_off, req_tokens, req_tenant, matched_len, ne
         _check(lib().skv_tree_insert(tree.handle, n_req, hp(a[0]), hp(a[1]), hp(a[2]), hp(a[3]), hp(a[4]),
                                      a[4].shape[1], hp(first), hp(n), _stream(stream)), "skv_tree_insert")
     return first, n
+
+
+def skv_set_epoch(tree: Tree, epoch: int):
+    _check(lib().skv_set_epoch(tree.handle, epoch), "skv_set_epoch")
+
+
+def skv_block_epochs_read(tree: Tree, epoch, stream=None):
+    assert epoch.dtype == torch.int32 and epoch.numel() >= tree.info()["n_in_blocks"]
+    _check(lib().skv_block_epochs_read(tree.handle, _dptr(epoch), _stream(stream)), "skv_block_epochs_read")
+
+
+def skv_evict(tree: Tree, n_want: int, protect_ids=(), stream=None):
+    """Returns (block ids, pages) of the evicted blocks, in eviction order (numpy int32)."""
+    prot = np.ascontiguousarray(protect_ids, dtype=np.int32)
+    ids = np.zeros(max(n_want, 1), dtype=np.int32)
+    pages = np.zeros(max(n_want, 1), dtype=np.int32)
+    k = C.c_int64()
+    hp = lambda x: C.c_void_p(x.ctypes.data) if x.size else None
+    with torch.cuda.device(tree.slab.device):
+        _check(lib().skv_evict(tree.handle, n_want, hp(prot), len(prot), hp(ids), hp(pages), C.byref(k),
+                               _stream(stream)), "skv_evict")
+    return ids[: k.value], pages[: k.value]
 
 
 def skv_match(tree: Tree, req_off, req_tokens, req_tenant, max_blocks, matched_len, page_table, stream=None):

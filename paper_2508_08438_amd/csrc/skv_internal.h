@@ -22,7 +22,7 @@ struct SkvNode {       // 16 bytes
 };
 struct SkvSlot {       // 16 bytes
   uint32_t hash_lo, hash_hi;
-  int32_t child;       // node index, -1 = empty
+  int32_t child;       // node index, -1 = empty, -2 = removed (probing goes on)
   int32_t pad;
 };
 #define SKV_CTR_STRIDE 8  // uint32 per block: [0] hit_cur, [1..4] tenant bitmap, [5] hit_pre, [6] u_pre, [7] predicate streak
@@ -34,9 +34,11 @@ struct SkvTreeDev {
   const int32_t* canon;   // [n_blocks]   input block id that created the entry
   const int32_t* flat_of; // [n_in_blocks] flat index of the entry an input block created, -1 if none
   uint32_t* ctr;          // [n_blocks][SKV_CTR_STRIDE]
+  uint32_t* epoch;        // [n_blocks]   epoch counter value at the block's last access
   const SkvNode* nodes;   // [n_nodes+1]
   const SkvSlot* slots;
-  int32_t n_blocks, n_nodes, n_tenants, n_pages;
+  int32_t n_blocks, n_nodes, n_tenants, n_pages;  // n_blocks: block records in use, evicted ones (canon < 0) included
+  uint32_t cur_epoch;     // stamped on every block a lookup matches
 };
 
 struct SkvHostMirror;  // host copy of the structure, kept for insertions

@@ -54,7 +54,7 @@ __device__ inline int find_child(const SkvTreeDev& t, const SkvNode nd, const in
     const bool valid = base + lane < nd.tab_cap;
     SkvSlot e{0, 0, -1, 0};
     if (valid) e = t.slots[nd.tab_off + (((uint32_t)h + (uint32_t)(base + lane)) & mask)];
-    const uint64_t empty = ballot64(valid && e.child < 0);
+    const uint64_t empty = ballot64(valid && e.child == -1);  // a removed entry (-2) does not end the probe
     uint64_t cand = ballot64(valid && e.child >= 0 && e.hash_lo == (uint32_t)h && e.hash_hi == (uint32_t)(h >> 32));
     if (empty) cand &= (empty & (~empty + 1)) - 1;  // only slots probed before the first empty one
     while (cand) {
@@ -128,6 +128,7 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
         uint32_t* ctr = t.ctr + (size_t)blk * SKV_CTR_STRIDE;
         atomicAdd(ctr, 1u);
         atomicOr(ctr + tword, tbit);
+        t.epoch[blk] = t.cur_epoch;  // every lookup of one batch writes the same value
       }
       j += take;
       if (take < cb) stop = true;

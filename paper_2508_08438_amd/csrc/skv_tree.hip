@@ -35,7 +35,7 @@ namespace {
 constexpr int64_t kMaxBlocks = 0x7fffffff / 32;
 
 struct Layout {  // byte offsets inside the slab
-  size_t tok, page, meta, canon, flat_of, ctr, nodes, slots, total;
+  size_t tok, page, meta, canon, flat_of, ctr, epoch, nodes, slots, total;
 };
 
 // Every array is sized for `cap` blocks: the entries the build creates plus room for later insertions.
@@ -54,6 +54,7 @@ Layout make_layout(size_t n_blocks, size_t n_in_blocks, size_t n_nodes_incl_root
   l.nodes = o; o = skv_align256(o + n_nodes_incl_root * sizeof(SkvNode));
   l.slots = o; o = skv_align256(o + (n_slots ? n_slots : 1) * sizeof(SkvSlot));
   l.ctr = o;   o = skv_align256(o + n_blocks * SKV_CTR_STRIDE * sizeof(uint32_t));
+  l.epoch = o; o = skv_align256(o + (n_blocks ? n_blocks : 1) * sizeof(uint32_t));
   l.total = o;
   return l;
 }
@@ -69,9 +70,14 @@ struct SkvHostMirror {
   size_t slots_used = 0;
   std::vector<SkvNode> nodes;         // [n_nodes + 1]
   std::vector<int32_t> kids;          // children per node
+  std::vector<int32_t> filled;        // table slots that are not empty (children + removed entries)
+  std::vector<int32_t> parent;        // parent node of every node (root: -1)
   std::vector<SkvSlot> slots;         // the arena up to slots_used
   std::vector<int32_t> tok;           // [n_blocks][16], flat order
+  std::vector<int32_t> canon, page;   // [n_blocks] input block id (-1 once evicted), page id
+  std::vector<int32_t> flat_of;       // [n_in_blocks]
   std::vector<uint8_t> page_used;     // [n_pages]
+  int64_t live_blocks = 0;
 };
 
 namespace {
@@ -109,6 +115,7 @@ __global__ void counters_scatter_kernel(SkvTreeDev t, uint32_t* hit, uint32_t* u
   for (int b = blockIdx.x * blockDim.x + threadIdx.x; b < t.n_blocks; b += gridDim.x * blockDim.x) {
     const uint32_t* c = t.ctr + (size_t)b * SKV_CTR_STRIDE;
     int id = t.canon[b];
+    if (id < 0) continue;  // evicted
     hit[id] = c[0];
     ucnt[id] = __popc(c[1]) + __popc(c[2]) + __popc(c[3]) + __popc(c[4]);
   }
@@ -127,7 +134,7 @@ __global__ void window_roll_kernel(SkvTreeDev t, skv_rdr_policy pol, int32_t* n_
   for (int b0 = blockIdx.x * blockDim.x; b0 < t.n_blocks; b0 += gridDim.x * blockDim.x) {
     const int b = b0 + threadIdx.x;
     bool demote = false;
-    if (b < t.n_blocks) {
+    if (b < t.n_blocks && t.canon[b] >= 0) {  // evicted records are skipped
       uint4* rec = (uint4*)(t.ctr + (size_t)b * SKV_CTR_STRIDE);
       const uint4 lo = rec[0], hi = rec[1];  // {hit, bm0, bm1, bm2}, {bm3, hit_pre, u_pre, streak}
       const uint32_t h = lo.x;
@@ -158,9 +165,17 @@ __global__ void block_state_scatter_kernel(SkvTreeDev t, uint8_t* priv, uint32_t
   for (int b = blockIdx.x * blockDim.x + threadIdx.x; b < t.n_blocks; b += gridDim.x * blockDim.x) {
     const uint32_t* c = t.ctr + (size_t)b * SKV_CTR_STRIDE;
     const int id = t.canon[b];
+    if (id < 0) continue;  // evicted
     if (priv) priv[id] = t.meta[b] < 0 ? 1 : 0;
     if (hit_pre) hit_pre[id] = c[5];
     if (u_pre) u_pre[id] = c[6];
+  }
+}
+
+__global__ void epoch_scatter_kernel(SkvTreeDev t, uint32_t* epoch) {
+  for (int b = blockIdx.x * blockDim.x + threadIdx.x; b < t.n_blocks; b += gridDim.x * blockDim.x) {
+    const int id = t.canon[b];
+    if (id >= 0) epoch[id] = t.epoch[b];
   }
 }
 
@@ -220,7 +235,6 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   parent.reserve(nib); src.reserve(nib); n_child.reserve(nib); only_child.reserve(nib); bhash.reserve(nib);
   const uint32_t cap = next_pow2((uint32_t)(2 * (size_t)nib + 2));
   std::vector<int32_t> table(cap, -1);
-  int32_t root_children = 0;
   for (int64_t s = 0; s < d->n_seq; ++s) {
     int32_t par = -1;
     for (int64_t b = d->seq_off[s] / 16; b < d->seq_off[s + 1] / 16; ++b) {
@@ -239,7 +253,7 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
         table[slot] = id;
         parent.push_back(par); src.push_back((int32_t)b); n_child.push_back(0);
         only_child.push_back(-1); bhash.push_back(hb);
-        if (par < 0) ++root_children; else { n_child[par]++; only_child[par] = id; }
+        if (par >= 0) { n_child[par]++; only_child[par] = id; }
       }
       par = id;
     }
@@ -337,6 +351,16 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   m->slots_used = n_slots;
   m->nodes = nodes;
   m->kids = kids;
+  m->filled = kids;
+  m->parent.assign(nodes.size(), -1);
+  for (int32_t n = 1; n <= n_nodes; ++n) {
+    const int32_t pb = parent[head_of_node[n]];
+    m->parent[n] = pb < 0 ? 0 : node_of[pb];
+  }
+  m->canon.assign(h_canon, h_canon + n_blocks);
+  m->page.assign(h_page, h_page + n_blocks);
+  m->flat_of.assign(h_flat_of, h_flat_of + nib);
+  m->live_blocks = n_blocks;
   m->slots.assign(slots.begin(), slots.begin() + n_slots);
   m->tok.assign(h_tok, h_tok + (size_t)n_blocks * 16);
   m->page_used.assign((size_t)d->n_pages, 0);
@@ -347,6 +371,8 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   t->dev.canon = (const int32_t*)(base + L.canon);
   t->dev.flat_of = (const int32_t*)(base + L.flat_of);
   t->dev.ctr = (uint32_t*)(base + L.ctr);
+  t->dev.epoch = (uint32_t*)(base + L.epoch);
+  t->dev.cur_epoch = 0;
   t->dev.nodes = (const SkvNode*)(base + L.nodes);
   t->dev.slots = (const SkvSlot*)(base + L.slots);
   t->dev.n_blocks = n_blocks;
@@ -360,6 +386,7 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   if (e == hipSuccess && cap_blocks) {  // counters of the whole capacity: inserted blocks start from zero
     size_t n = (size_t)cap_blocks * SKV_CTR_STRIDE;
     fill_u32_kernel<<<grid_for(n, 256), 256, 0, st>>>(t->dev.ctr, n, 0u);
+    fill_u32_kernel<<<grid_for((size_t)cap_blocks, 256), 256, 0, st>>>(t->dev.epoch, (size_t)cap_blocks, 0u);
     e = hipGetLastError();
   }
   if (e == hipSuccess) e = hipStreamSynchronize(st);
@@ -392,16 +419,17 @@ struct Inserter {
     if (!n.tab_cap) return -1;
     for (uint32_t s = (uint32_t)h & (uint32_t)(n.tab_cap - 1);; s = (s + 1) & (uint32_t)(n.tab_cap - 1)) {
       const SkvSlot& sl = m->slots[(size_t)n.tab_off + s];
-      if (sl.child < 0) return -1;
-      if (sl.hash_lo == (uint32_t)h && sl.hash_hi == (uint32_t)(h >> 32) &&
+      if (sl.child == -1) return -1;
+      if (sl.child >= 0 && sl.hash_lo == (uint32_t)h && sl.hash_hi == (uint32_t)(h >> 32) &&
           !memcmp(&m->tok[(size_t)m->nodes[sl.child].first * 16], blk, 64))
         return sl.child;
     }
   }
-  void put(int32_t node, uint64_t h, int32_t child) {
+  void put(int32_t node, uint64_t h, int32_t child) {  // into the first empty or removed slot of the probe sequence
     const SkvNode& n = m->nodes[node];
     uint32_t s = (uint32_t)h & (uint32_t)(n.tab_cap - 1);
     while (m->slots[(size_t)n.tab_off + s].child >= 0) s = (s + 1) & (uint32_t)(n.tab_cap - 1);
+    if (m->slots[(size_t)n.tab_off + s].child == -1) m->filled[node]++;
     m->slots[(size_t)n.tab_off + s] = SkvSlot{(uint32_t)h, (uint32_t)(h >> 32), child, 0};
     touch_slot((size_t)n.tab_off + s);
   }
@@ -409,7 +437,7 @@ struct Inserter {
   bool add_child(int32_t node, uint64_t h, int32_t child) {
     SkvNode& n = m->nodes[node];
     const int32_t kids = m->kids[node] + 1;
-    if (2 * kids > n.tab_cap) {
+    if (2 * (m->filled[node] + 1) > n.tab_cap) {  // removed entries count: a probe must always reach an empty slot
       const int32_t cap = (int32_t)next_pow2((uint32_t)(2 * kids) < 4u ? 4u : (uint32_t)(2 * kids));
       if (m->slots_used + (size_t)cap > slots_for((size_t)m->cap_blocks)) return false;
       const SkvNode old = n;
@@ -419,6 +447,7 @@ struct Inserter {
       m->slots.resize(m->slots_used, SkvSlot{0, 0, -1, 0});
       touch_slot((size_t)n.tab_off);
       touch_slot(m->slots_used - 1);
+      m->filled[node] = 0;
       for (int32_t i = 0; i < old.tab_cap; ++i) {
         const SkvSlot sl = m->slots[(size_t)old.tab_off + i];
         if (sl.child >= 0) put(node, ((uint64_t)sl.hash_hi << 32) | sl.hash_lo, sl.child);
@@ -450,10 +479,17 @@ struct Inserter {
         const int32_t tail = (int32_t)m->nodes.size();
         m->nodes.push_back(SkvNode{run.first + (int32_t)j, run.n_blocks - (int32_t)j, run.tab_off, run.tab_cap});
         m->kids.push_back(m->kids[c]);
+        m->filled.push_back(m->filled[c]);
+        m->parent.push_back(c);
+        for (int32_t q = 0; q < run.tab_cap; ++q) {  // the children move below the new node
+          const int32_t gc = m->slots[(size_t)run.tab_off + q].child;
+          if (gc >= 0) m->parent[gc] = tail;
+        }
         m->nodes[c].n_blocks = (int32_t)j;
         m->nodes[c].tab_off = 0;
         m->nodes[c].tab_cap = 0;
         m->kids[c] = 0;
+        m->filled[c] = 0;
         touch_node((size_t)c);
         touch_node((size_t)tail);
         if (!add_child(c, skv_hash_block_host(&m->tok[((size_t)run.first + j) * 16]), tail)) return -1;
@@ -470,12 +506,17 @@ struct Inserter {
     const int32_t fresh = (int32_t)m->nodes.size();
     m->nodes.push_back(SkvNode{(int32_t)n_blocks, (int32_t)add, 0, 0});
     m->kids.push_back(0);
+    m->filled.push_back(0);
+    m->parent.push_back(node);
     touch_node((size_t)fresh);
     if (!add_child(node, skv_hash_block_host(x + i * 16), fresh)) return -1;
     m->tok.insert(m->tok.end(), x + i * 16, x + nb * 16);
     for (int64_t j = i; j < nb; ++j) {
       page.push_back(pages[j - k_vis]);
       meta.push_back((int32_t)0x80000000 | tenant);
+      m->page.push_back(pages[j - k_vis]);
+      m->canon.push_back((int32_t)(n_in + (j - i)));
+      m->flat_of.push_back((int32_t)(n_blocks + (j - i)));
       m->page_used[pages[j - k_vis]] = 1;
     }
     n_blocks += add;
@@ -518,7 +559,8 @@ extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_of
   const std::vector<int32_t> kids0 = m->kids;
   const std::vector<SkvSlot> slots0 = m->slots;
   const std::vector<uint8_t> used0 = m->page_used;
-  const size_t slots_used0 = m->slots_used, tok0 = m->tok.size();
+  const std::vector<int32_t> filled0 = m->filled, parent0 = m->parent;
+  const size_t slots_used0 = m->slots_used, tok0 = m->tok.size(), blocks0 = m->canon.size(), in0 = m->flat_of.size();
   Inserter ins{t, m, t->dev.n_blocks, t->n_in_blocks, {}, {}, SIZE_MAX, 0, SIZE_MAX, 0};
   bool full = false;
   for (int32_t r = 0; r < n_req && !full; ++r) {
@@ -534,7 +576,9 @@ extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_of
   }
   if (full) {
     m->nodes = nodes0; m->kids = kids0; m->slots = slots0; m->page_used = used0;
+    m->filled = filled0; m->parent = parent0;
     m->slots_used = slots_used0; m->tok.resize(tok0);
+    m->canon.resize(blocks0); m->page.resize(blocks0); m->flat_of.resize(in0);
     return SKV_ENOMEM;
   }
   // upload: the appended block records, then the spans of node and slot records that changed
@@ -549,6 +593,8 @@ extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_of
     SKV_HIP(hipMemcpyAsync(base + m->L.meta + (size_t)nb0 * 4, ins.meta.data(), (size_t)add * 4, hipMemcpyHostToDevice, st));
     SKV_HIP(hipMemcpyAsync(base + m->L.canon + (size_t)nb0 * 4, canon.data(), (size_t)add * 4, hipMemcpyHostToDevice, st));
     SKV_HIP(hipMemcpyAsync(base + m->L.flat_of + (size_t)nin0 * 4, flat_of.data(), (size_t)add * 4, hipMemcpyHostToDevice, st));
+    fill_u32_kernel<<<grid_for((size_t)add, 256), 256, 0, st>>>(t->dev.epoch + nb0, (size_t)add, t->dev.cur_epoch);
+    SKV_HIP(hipGetLastError());
     SKV_HIP(hipStreamSynchronize(st));  // the staging vectors die with this scope
   }
   if (ins.node_hi > ins.node_lo)
@@ -561,13 +607,107 @@ extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_of
   t->dev.n_blocks = (int32_t)ins.n_blocks;
   t->dev.n_nodes = (int32_t)m->nodes.size() - 1;
   t->n_in_blocks = ins.n_in;
+  m->live_blocks += add;
+  return SKV_OK;
+}
+
+// ---- eviction (Section 4.3.1 Evict: epoch-based LRU; Section 4.3.2 progressive eviction) ----
+extern "C" int skv_set_epoch(skv_tree* t, uint32_t epoch) {
+  if (!t) return SKV_EINVAL;
+  t->dev.cur_epoch = epoch;
+  return SKV_OK;
+}
+
+extern "C" int skv_block_epochs_read(skv_tree* t, uint32_t* d_epoch, void* stream) {
+  if (!t || !d_epoch) return SKV_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  if (t->n_in_blocks) fill_u32_kernel<<<grid_for((size_t)t->n_in_blocks, 256), 256, 0, st>>>(d_epoch, (size_t)t->n_in_blocks, 0u);
+  if (t->dev.n_blocks) epoch_scatter_kernel<<<grid_for((size_t)t->dev.n_blocks, 256), 256, 0, st>>>(t->dev, d_epoch);
+  SKV_HIP(hipGetLastError());
+  return SKV_OK;
+}
+
+extern "C" int skv_evict(skv_tree* t, int64_t n_want, const int32_t* protect_ids, int64_t n_protect,
+                         int32_t* evicted_ids, int32_t* evicted_pages, int64_t* n_evicted, void* stream) {
+  if (!t || !t->host || n_want < 0 || n_protect < 0 || !n_evicted) return SKV_EINVAL;
+  if (n_protect > 0 && !protect_ids) return SKV_EINVAL;
+  if (n_want > 0 && (!evicted_ids || !evicted_pages)) return SKV_EINVAL;
+  *n_evicted = 0;
+  SkvHostMirror* m = t->host;
+  const int64_t nb = t->dev.n_blocks;
+  if (n_want == 0 || nb == 0) return SKV_OK;
+  hipStream_t st = (hipStream_t)stream;
+  std::vector<uint32_t> epoch((size_t)nb);
+  SKV_HIP(hipMemcpyAsync(epoch.data(), t->dev.epoch, (size_t)nb * 4, hipMemcpyDeviceToHost, st));
+  SKV_HIP(hipStreamSynchronize(st));
+  std::vector<uint8_t> prot((size_t)t->n_in_blocks, 0);
+  for (int64_t i = 0; i < n_protect; ++i)
+    if (protect_ids[i] >= 0 && protect_ids[i] < t->n_in_blocks) prot[protect_ids[i]] = 1;
+  // candidates: the last block of every childless node, oldest (epoch, block id) first
+  struct Cand { uint32_t epoch; int32_t id, node; };
+  auto later = [](const Cand& a, const Cand& b) { return a.epoch != b.epoch ? a.epoch > b.epoch : a.id > b.id; };
+  std::vector<Cand> heap;
+  auto push_tail = [&](int32_t n) {
+    const SkvNode& nd = m->nodes[n];
+    const int32_t f = nd.first + nd.n_blocks - 1;
+    heap.push_back(Cand{epoch[f], m->canon[f], n});
+    std::push_heap(heap.begin(), heap.end(), later);
+  };
+  for (int32_t n = 1; n < (int32_t)m->nodes.size(); ++n)
+    if (m->kids[n] == 0 && m->nodes[n].n_blocks > 0) push_tail(n);
+  size_t node_lo = SIZE_MAX, node_hi = 0, slot_lo = SIZE_MAX, slot_hi = 0, blk_lo = SIZE_MAX, blk_hi = 0, id_lo = SIZE_MAX, id_hi = 0;
+  int64_t done = 0;
+  while (done < n_want && !heap.empty()) {
+    std::pop_heap(heap.begin(), heap.end(), later);
+    const Cand c = heap.back();
+    heap.pop_back();
+    if (prot[c.id]) continue;  // in use: this node keeps its tail, and with it everything above
+    SkvNode& nd = m->nodes[c.node];
+    const int32_t f = nd.first + nd.n_blocks - 1;
+    evicted_ids[done] = c.id;
+    evicted_pages[done] = m->page[f];
+    ++done;
+    m->page_used[m->page[f]] = 0;
+    m->canon[f] = -1;
+    m->flat_of[c.id] = -1;
+    blk_lo = std::min(blk_lo, (size_t)f); blk_hi = std::max(blk_hi, (size_t)f + 1);
+    id_lo = std::min(id_lo, (size_t)c.id); id_hi = std::max(id_hi, (size_t)c.id + 1);
+    nd.n_blocks--;
+    node_lo = std::min(node_lo, (size_t)c.node); node_hi = std::max(node_hi, (size_t)c.node + 1);
+    if (nd.n_blocks > 0) { push_tail(c.node); continue; }
+    // the node is gone: its entry in the parent's table becomes a removed slot
+    const int32_t p = m->parent[c.node];
+    const SkvNode& pn = m->nodes[p];
+    for (int32_t q = 0; q < pn.tab_cap; ++q) {
+      SkvSlot& sl = m->slots[(size_t)pn.tab_off + q];
+      if (sl.child == c.node) {
+        sl.child = -2;
+        slot_lo = std::min(slot_lo, (size_t)pn.tab_off + q); slot_hi = std::max(slot_hi, (size_t)pn.tab_off + q + 1);
+        break;
+      }
+    }
+    m->kids[p]--;
+    if (m->kids[p] == 0 && p != 0 && pn.n_blocks > 0) push_tail(p);
+  }
+  *n_evicted = done;
+  m->live_blocks -= done;
+  if (!done) return SKV_OK;
+  char* base = m->base;
+  SKV_HIP(hipMemcpyAsync(base + m->L.canon + blk_lo * 4, &m->canon[blk_lo], (blk_hi - blk_lo) * 4, hipMemcpyHostToDevice, st));
+  SKV_HIP(hipMemcpyAsync(base + m->L.flat_of + id_lo * 4, &m->flat_of[id_lo], (id_hi - id_lo) * 4, hipMemcpyHostToDevice, st));
+  SKV_HIP(hipMemcpyAsync(base + m->L.nodes + node_lo * sizeof(SkvNode), &m->nodes[node_lo],
+                         (node_hi - node_lo) * sizeof(SkvNode), hipMemcpyHostToDevice, st));
+  if (slot_hi > slot_lo)
+    SKV_HIP(hipMemcpyAsync(base + m->L.slots + slot_lo * sizeof(SkvSlot), &m->slots[slot_lo],
+                           (slot_hi - slot_lo) * sizeof(SkvSlot), hipMemcpyHostToDevice, st));
+  SKV_HIP(hipStreamSynchronize(st));
   return SKV_OK;
 }
 
 extern "C" int skv_tree_info(const skv_tree* t, int64_t* n_nodes, int64_t* n_blocks, int64_t* n_in_blocks) {
   if (!t) return SKV_EINVAL;
   if (n_nodes) *n_nodes = t->dev.n_nodes;
-  if (n_blocks) *n_blocks = t->dev.n_blocks;
+  if (n_blocks) *n_blocks = t->host ? t->host->live_blocks : t->dev.n_blocks;
   if (n_in_blocks) *n_in_blocks = t->n_in_blocks;
   return SKV_OK;
 }

@@ -666,3 +666,121 @@ def test_insert_configs_full_size(name):
             assert np.all(ml2 >= mlen)   # (many requests stop at other tenants' private blocks, before and after)
             print(f"   reuse before {int(mlen.sum())} tokens, after {int(ml2.sum())}", flush=True)
     compare_state(skv, dtree, otree, name)
+
+
+# ---------------------------------------------------------------------------------------------
+# eviction (Section 4.3.1 Evict, Section 4.3.2 progressive eviction): epochs stamped by the match kernel,
+# then the same victims in the same order as the oracle, and identical lookups afterwards
+
+def device_epochs(skv, dtree):
+    n = dtree.info()["n_in_blocks"]
+    e = torch.zeros(max(n, 1), dtype=torch.int32, device="cuda:0")
+    skv.skv_block_epochs_read(dtree, e)
+    torch.cuda.synchronize()
+    return e[:n].cpu().numpy().view(np.uint32)
+
+
+def run_evict_stream(seed, n_rounds=5, n_req=10):
+    from test_oracle_insert import make_round
+    skv = _skv()
+    block_vocab = 3 if seed % 3 == 0 else None
+    w = inputs.small_random(seed=seed, n_req=8, p_sens=0.4, n_tenants=3, block_vocab=block_vocab)
+    vocab = int(w.seq_tokens.max()) + 1 if len(w.seq_tokens) else 2
+    otree = oracle.OracleTree.from_workload(w)
+    dtree = skv.skv_tree_build(w.seq_tokens, w.seq_off, w.blk_sensitive, w.blk_owner, w.blk_page, w.n_tenants,
+                               w.n_pages + 4096, device="cuda:0", reserve_blocks=1024)
+    g = np.random.default_rng(2000 + seed)
+    free_pages = list(range(w.n_pages, w.n_pages + 4096))[::-1]
+    earlier = [w.req_tokens[w.req_off[r]: w.req_off[r + 1]] for r in range(w.n_req)]
+    evicted = 0
+    for rnd in range(n_rounds):
+        otree.set_epoch(rnd + 1)
+        skv.skv_set_epoch(dtree, rnd + 1)
+        reqs, off, toks, tenants = make_round(g, earlier, vocab, w.n_tenants, n_req, block_vocab)
+        mb = max(max(len(x) // B for x in reqs), 1)
+        mlen, pt = device_match(skv, dtree, off, toks, tenants, mb)
+        o_mlen, o_pt, o_ids = otree.match(off, toks, tenants, mb, want_ids=True)
+        assert np.array_equal(mlen, o_mlen) and np.array_equal(pt, o_pt), (seed, rnd)
+        new_pages = np.full((n_req, mb + 1), -1, np.int32)
+        for r, x in enumerate(reqs):
+            for j in range(len(x) // B - mlen[r] // B):
+                new_pages[r, j] = free_pages.pop()
+        first, n = skv.skv_tree_insert(dtree, off, toks, tenants, mlen, new_pages)
+        o_first, o_n = otree.insert(off, toks, tenants, mlen, new_pages)
+        assert np.array_equal(first, o_first) and np.array_equal(n, o_n), (seed, rnd)
+        assert np.array_equal(device_epochs(skv, dtree), otree.epochs()), (seed, rnd)
+        protect = o_ids[o_ids >= 0][:: int(g.integers(1, 4))].astype(np.int32)
+        n_want = int(g.integers(0, max(otree.n_blocks // 3, 1) + 1))
+        ids, pages = skv.skv_evict(dtree, n_want, protect)
+        want_ids, want_pages = otree.evict(n_want, protect)
+        assert np.array_equal(ids, want_ids) and np.array_equal(pages, want_pages), (seed, rnd)
+        evicted += len(ids)
+        free_pages += [int(p) for p in pages]              # evicted pages are handed out again
+        earlier += reqs
+        for t in range(w.n_tenants):
+            sample = [earlier[i] for i in g.choice(len(earlier), min(24, len(earlier)), replace=False)]
+            o = np.concatenate([[0], np.cumsum([len(x) for x in sample])]).astype(np.int32)
+            tk = np.concatenate(sample + [np.zeros(0, np.int32)]).astype(np.int32)
+            ten = np.full(len(sample), t, np.int32)
+            mb2 = max(max(len(x) // B for x in sample), 1)
+            ml2, pt2 = device_match(skv, dtree, o, tk, ten, mb2)
+            o_ml2, o_pt2 = otree.match(o, tk, ten, mb2)
+            assert np.array_equal(ml2, o_ml2) and np.array_equal(pt2, o_pt2), (seed, rnd, t)
+        compare_state(skv, dtree, otree, (seed, rnd))
+        assert np.array_equal(device_epochs(skv, dtree), otree.epochs()), (seed, rnd)
+    return evicted
+
+
+def test_evict_stream_small_cases():
+    total = 0
+    for seed in range(30):
+        print(f"[evict] stream {seed}", flush=True)
+        total += run_evict_stream(seed)
+    assert total > 500
+
+
+def test_evict_config3_then_reinsert():
+    """Full size: half of config 3's requests touch the tree at epoch 1, then 1500 blocks are evicted with the
+    touched blocks protected; victims, pages and all later lookups agree with the oracle; the evicted pages are
+    then handed to an insert, which must accept them."""
+    skv = _skv()
+    w = inputs.config3()
+    otree = oracle.OracleTree.from_workload(w)
+    dtree = skv.skv_tree_build(w.seq_tokens, w.seq_off, w.blk_sensitive, w.blk_owner, w.blk_page, w.n_tenants,
+                               w.n_pages, device="cuda:0", reserve_blocks=4096)
+    mb = max(w.max_blocks, 1)
+    half = w.n_req // 2
+    off, ten = w.req_off[: half + 1], w.req_tenant[:half]
+    toks = w.req_tokens[: off[-1]]
+    otree.set_epoch(1)
+    skv.skv_set_epoch(dtree, 1)
+    mlen, pt = device_match(skv, dtree, off, toks, ten, mb)
+    o_mlen, o_pt, o_ids = otree.match(off, toks, ten, mb, want_ids=True)
+    assert np.array_equal(mlen, o_mlen) and np.array_equal(pt, o_pt)
+    assert np.array_equal(device_epochs(skv, dtree), otree.epochs())
+    protect = np.unique(o_ids[o_ids >= 0]).astype(np.int32)
+    print(f"[evict] c3: {otree.n_blocks} blocks, {len(protect)} protected", flush=True)
+    ids, pages = skv.skv_evict(dtree, 1500, protect)
+    want_ids, want_pages = otree.evict(1500, protect)
+    assert len(ids) == 1500 and np.array_equal(ids, want_ids) and np.array_equal(pages, want_pages)
+    ml2, pt2 = device_match(skv, dtree, w.req_off, w.req_tokens, w.req_tenant, mb)
+    o_ml2, o_pt2 = otree.match(w.req_off, w.req_tokens, w.req_tenant, mb)
+    assert np.array_equal(ml2, o_ml2) and np.array_equal(pt2, o_pt2)
+    # the second half's suffixes go into the freed pages
+    off2 = (w.req_off[half:] - w.req_off[half]).astype(np.int32)
+    toks2, ten2 = w.req_tokens[w.req_off[half]:], w.req_tenant[half:]
+    ml3 = ml2[half:]
+    need = np.minimum(np.diff(off2) // B - ml3 // B, 8)      # up to 8 new blocks per request
+    new_pages = np.full((len(ten2), 8), -1, np.int32)
+    pool = [int(p) for p in pages]
+    for r in range(len(ten2)):
+        for j in range(int(need[r])):
+            if pool:
+                new_pages[r, j] = pool.pop()
+    first, n = skv.skv_tree_insert(dtree, off2, toks2, ten2, ml3, new_pages)
+    o_first, o_n = otree.insert(off2, toks2, ten2, ml3, new_pages)
+    assert np.array_equal(first, o_first) and np.array_equal(n, o_n)
+    ml4, pt4 = device_match(skv, dtree, w.req_off, w.req_tokens, w.req_tenant, mb)
+    o_ml4, o_pt4 = otree.match(w.req_off, w.req_tokens, w.req_tenant, mb)
+    assert np.array_equal(ml4, o_ml4) and np.array_equal(pt4, o_pt4)
+    compare_state(skv, dtree, otree, "c3")
