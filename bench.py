@@ -120,6 +120,7 @@ def main():
     ap.add_argument("--calib-mib", type=int, default=0,
                     help="also run one plain streaming kernel (out = 2 * in over this many MiB of fp32) outside the "
                          "timed region, as the known-size reference for HBM traffic counters")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-step attention measurement")
     ap.add_argument("--cpu-rows", type=int, default=262144, help="oracle attention rows to time (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -197,6 +198,36 @@ def main():
         t_scatter = sg[0].elapsed_time(sg[1]) * 1e-3 / 10
         del kp2, vp2
 
+    # decode step, outside the timed region and on its own workload: 64 requests, contexts 4096..16384 tokens
+    decode = None
+    if not args.no_decode and w.attn.dtype == "bf16":
+        dw = inputs.decode_workload()
+        da = dw.attn
+        dshape = (dw.n_pages, 16, da.n_kv_heads, da.head_dim)
+        dk = torch.empty(dshape, dtype=da.torch_dtype, device=sess.device)
+        dv = torch.empty(dshape, dtype=da.torch_dtype, device=sess.device)
+        dw.fill_pool("k", dk)
+        dw.fill_pool("v", dv)
+        dq = dw.queries(sess.device)
+        dout = torch.zeros_like(dq)
+        ddesc = skv.attn_desc(da.n_q_heads, da.n_kv_heads, da.head_dim, da.dtype, da.scale)
+        dws = torch.zeros(skv.skv_decode_attn_workspace_size(ddesc, dw.n_req, dw.max_blocks), dtype=torch.uint8,
+                          device=sess.device)
+        dctx = torch.from_numpy(dw.ctx_len).to(sess.device)
+        dpt = torch.from_numpy(dw.page_table).to(sess.device)
+        for _ in range(3):
+            skv.skv_decode_attn(ddesc, dq, dk, dv, dctx, dpt, dw.max_blocks, dout, dws)
+        sg[0].record()
+        for _ in range(20):
+            skv.skv_decode_attn(ddesc, dq, dk, dv, dctx, dpt, dw.max_blocks, dout, dws)
+        sg[1].record()
+        torch.cuda.synchronize()
+        t_dec = sg[0].elapsed_time(sg[1]) * 1e-3 / 20
+        dbytes = float(dw.ctx_len.sum()) * 2 * da.n_kv_heads * da.head_dim * 2    # every cached K and V byte once
+        decode = {"requests": dw.n_req, "cached_tokens": int(dw.ctx_len.sum()), "ms": t_dec * 1e3,
+                  "tokens_per_s": dw.n_req / t_dec, "gbs": dbytes / t_dec / 1e9, "frac_of_hbm_peak": dbytes / t_dec / 8e12}
+        del dk, dv
+
     tokens = float(len(w.req_tokens))
     pt = sess.page_table.cpu().numpy()
     flops = attention_flops(w, mlen)
@@ -225,6 +256,7 @@ def main():
             "pages": n_new, "ms": t_scatter * 1e3,
             "gbs": 2.0 * n_new * 16 * 2 * w.attn.n_kv_heads * w.attn.head_dim * (4 if w.attn.dtype == "f32" else 2)
             / t_scatter / 1e9},
+        "decode": decode,
         "roofline": {"bound": "mfma" if a.dtype == "bf16" else "alu", "kernel": "attn_bf16_kernel"
                      if a.dtype == "bf16" else "attn_f32_kernel", "achieved": achieved, "peak": peak,
                      "unit": "TFLOP/s", "frac": achieved / peak,

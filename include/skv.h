@@ -262,6 +262,22 @@ int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const void* d_q, 
                      const int32_t* d_matched_len, const int32_t* d_page_table, int32_t max_blocks,
                      void* d_out, void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* Decode-step attention (Section 2.1: at every decode step the new token attends to the cached K/V of all
+ * earlier tokens).  For request r, d_q holds one query row per query head ([n_req][n_q_heads][head_dim]) and
+ * d_ctx_len[r] the number of cached tokens it attends to (the current token's K/V included, already written
+ * to the pool); token j lives in page d_page_table[r*max_blocks + j/16], row j%16.
+ * d_out[r][h] = sum_j softmax_j(scale * q[r][h] . K[j]) V[j] over j < ctx_len[r], kv head h / (n_q_heads /
+ * n_kv_heads).  bf16, head_dim 128, at most 16 query heads per kv head (SKV_EINVAL otherwise).  ctx_len is
+ * clamped to [0, 16*max_blocks]; a request with no cached token gets zeros; a page id outside [0, n_pages)
+ * reads as zeros; rows of the last page beyond ctx_len are never used, whatever they hold.  Pools of several
+ * layers are handled by passing the layer's base pointers.  The workspace (device, 16-byte aligned,
+ * skv_decode_attn_workspace_size bytes) holds the partial softmax states of the key splits; it is overwritten
+ * by every call.  Errors as skv_prefill_attn. */
+int skv_decode_attn_workspace_size(const skv_attn_desc* desc, int32_t n_req, int32_t max_blocks, size_t* bytes);
+int skv_decode_attn(const skv_attn_desc* desc, int32_t n_req, const void* d_q, const void* d_kpool,
+                    const void* d_vpool, int32_t n_pages, const int32_t* d_ctx_len, const int32_t* d_page_table,
+                    int32_t max_blocks, void* d_out, void* d_workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ SKV_OK, SKV_EINVAL, SKV_ENOMEM, SKV_ERANGE, SKV_EHIP = 0, -1, -2, -3, -4
 EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_size_for_capacity", "skv_tree_build", "skv_tree_insert", "skv_set_epoch", "skv_block_epochs_read", "skv_evict",
            "skv_tree_info", "skv_tree_destroy", "skv_match", "skv_counters_read",
            "skv_counters_reset", "skv_window_roll", "skv_promote", "skv_block_state_read", "skv_suffix_offsets", "skv_gather_kv",
-           "skv_scatter_kv",
+           "skv_scatter_kv", "skv_decode_attn_workspace_size", "skv_decode_attn",
            "skv_prefill_attn_workspace_size", "skv_prefill_attn"]
 
 
@@ -73,6 +73,8 @@ def lib():
         l.skv_window_roll.argtypes = [vp, C.POINTER(RdrPolicy), vp, vp]
         l.skv_block_state_read.argtypes = [vp, vp, vp, vp, vp]
         l.skv_promote.argtypes = [vp, vp, i32, vp]
+        l.skv_decode_attn_workspace_size.argtypes = [C.POINTER(AttnDesc), i32, i32, C.POINTER(C.c_size_t)]
+        l.skv_decode_attn.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, vp, i32, vp, vp, i32, vp, vp, C.c_size_t, vp]
         l.skv_set_epoch.argtypes = [vp, C.c_uint32]
         l.skv_block_epochs_read.argtypes = [vp, vp, vp]
         l.skv_evict.argtypes = [vp, C.c_int64, vp, C.c_int64, vp, vp, C.POINTER(C.c_int64), vp]
@@ -291,3 +293,18 @@ def skv_prefill_attn(desc: AttnDesc, q, knew, vnew, q_off, kpool, vpool, matched
                                   _dptr(page_table), max_blocks, _dptr(out), _dptr(workspace),
                                   workspace.numel() * workspace.element_size(), _stream(stream)),
            "skv_prefill_attn")
+
+
+def skv_decode_attn_workspace_size(desc: AttnDesc, n_req, max_blocks) -> int:
+    n = C.c_size_t()
+    _check(lib().skv_decode_attn_workspace_size(C.byref(desc), n_req, max_blocks, C.byref(n)),
+           "skv_decode_attn_workspace_size")
+    return n.value
+
+
+def skv_decode_attn(desc: AttnDesc, q, kpool, vpool, ctx_len, page_table, max_blocks, out, workspace, stream=None):
+    n_req = ctx_len.numel()
+    assert q.shape[0] == n_req and out.shape == q.shape and ctx_len.dtype == page_table.dtype == torch.int32
+    _check(lib().skv_decode_attn(C.byref(desc), n_req, _dptr(q), _dptr(kpool), _dptr(vpool), kpool.shape[0],
+                                 _dptr(ctx_len), _dptr(page_table), max_blocks, _dptr(out), _dptr(workspace),
+                                 workspace.numel(), _stream(stream)), "skv_decode_attn")

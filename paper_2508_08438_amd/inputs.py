@@ -356,3 +356,62 @@ def small_random(seed: int, n_seq: int = 6, max_blocks: int = 8, vocab: int = 3,
 
 
 CONFIGS = {"c1": config1, "c2": config2, "c3": config3, "c4": config4, "c5": config5}
+
+
+@dataclass
+class DecodeWorkload:
+    """One decode step over a paged cache: per request a context length and the pages that hold it.
+    Pool and query values are the same pure functions of the element index as everywhere else."""
+    seed: int
+    attn: AttnShape
+    n_pages: int
+    ctx_len: np.ndarray      # int32 [R]: cached tokens the new token attends to (itself included)
+    page_table: np.ndarray   # int32 [R, max_blocks], -1 beyond the context
+    value_sigma: float
+
+    @property
+    def n_req(self) -> int:
+        return len(self.ctx_len)
+
+    @property
+    def max_blocks(self) -> int:
+        return self.page_table.shape[1]
+
+    def pool_pages(self, which: str, page_lo: int, page_hi: int, device="cpu") -> torch.Tensor:
+        a = self.attn
+        pe = BLOCK * a.n_kv_heads * a.head_dim
+        v = synth_values(self.seed, STREAM_KPOOL if which == "k" else STREAM_VPOOL, page_lo * pe,
+                         (page_hi - page_lo) * pe, self.value_sigma, device)
+        return v.to(a.torch_dtype).view(page_hi - page_lo, BLOCK, a.n_kv_heads, a.head_dim)
+
+    def fill_pool(self, which: str, out: torch.Tensor, pages=None, chunk_pages: int = 4096):
+        if pages is None:
+            for lo in range(0, self.n_pages, chunk_pages):
+                hi = min(self.n_pages, lo + chunk_pages)
+                out[lo:hi] = self.pool_pages(which, lo, hi, out.device)
+        else:
+            for p in np.unique(np.asarray(pages, dtype=np.int64)):
+                out[int(p)] = self.pool_pages(which, int(p), int(p) + 1, out.device)[0]
+        return out
+
+    def queries(self, device="cpu") -> torch.Tensor:
+        a = self.attn
+        n = self.n_req * a.n_q_heads * a.head_dim
+        return synth_values(self.seed, STREAM_Q, 0, n, self.value_sigma, device).to(a.torch_dtype).view(
+            self.n_req, a.n_q_heads, a.head_dim)
+
+
+def decode_workload(seed: int = 0x5AFE0006, n_req: int = 64, ctx_lo: int = 4096, ctx_hi: int = 16384,
+                    attn: Optional[AttnShape] = None, hard: bool = False, ctx=None) -> DecodeWorkload:
+    """Decode step of a serving batch: contexts uniform in [ctx_lo, ctx_hi] (or the listed ones), every page
+    used once, page ids a seeded permutation of the pool."""
+    attn = attn or AttnShape(32, 8, 128, "bf16")
+    g = _rng(seed, 0)
+    ctx_len = (np.asarray(ctx, dtype=np.int32) if ctx is not None
+               else g.integers(ctx_lo, ctx_hi + 1, n_req).astype(np.int32))
+    nb = (ctx_len + BLOCK - 1) // BLOCK
+    n_pages = int(nb.sum()) + 8
+    perm = g.permutation(n_pages).astype(np.int32)
+    table = np.full((len(ctx_len), max(int(nb.max()), 1)), -1, np.int32)
+    table[np.arange(table.shape[1])[None, :] < nb[:, None]] = perm[: int(nb.sum())]
+    return DecodeWorkload(seed, attn, n_pages, ctx_len, table, _sigma(attn, hard))
