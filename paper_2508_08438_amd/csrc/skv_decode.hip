@@ -53,8 +53,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attn_kernel(DecParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15;   // column of the MFMA tiles: the query head
   const int g4 = lane >> 4;    // lane group: keys 4 g4 .. 4 g4 + 3 of the wavefront's 16
-  const int split = blockIdx.x % p.n_splits;
-  const int kvh = (blockIdx.x / p.n_splits) % p.Hkv;
+  // kv head fastest: the workgroups that read the same pages (each its own 256-byte slice of every token row)
+  // are dispatched together, one per XCD, and walk the pages at the same time
+  const int kvh = blockIdx.x % p.Hkv;
+  const int split = (blockIdx.x / p.Hkv) % p.n_splits;
   const int r = blockIdx.x / (p.n_splits * p.Hkv);
   const int G = p.G;
   int ctx = __builtin_amdgcn_readfirstlane(p.ctx_len[r]);
@@ -117,25 +119,25 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attn_kernel(DecParams p) {
   // ---- global -> registers -> LDS: 16 threads x 16 B per key row, four 16-key groups per tile.  Buffer
   // loads check each lane's offset against the bytes that exist from the group's base on, so the rows of
   // the last page past ctx come back as zeros, whatever the pool holds there.
-  u32x4 kreg[4], vreg[4];
+  u32x4 kregA[4], vregA[4], kregB[4], vregB[4];  // two tiles in flight: kt+1 (landed or landing) and kt+2
   const int t_row = tid >> 4;
   const unsigned t_off = (unsigned)t_row * row_bytes + (unsigned)(tid & 15) * 16u;
-  auto load_tile = [&](int kt) __attribute__((always_inline)) {
+  auto load_tile = [&](int kt, u32x4 (&kreg)[4], u32x4 (&vreg)[4], uint64_t ak_w, uint64_t av_w) __attribute__((always_inline)) {
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc) {
       const int idx = (((kt - t0) & 15) << 2) + cc;
       int n_valid = ctx - (kt * kBN + cc * 16);  // clamped to 0..16 on the scalar unit
       asm("s_max_i32 %0, %1, 0\n\ts_min_i32 %0, %0, 16" : "=s"(n_valid) : "s"(n_valid) : "scc");
       const int nrec = n_valid * (int)row_bytes;
-      const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(lane_bcast(ak_cur, idx), 0, nrec, 0x00020000);
-      const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(lane_bcast(av_cur, idx), 0, nrec, 0x00020000);
+      const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(lane_bcast(ak_w, idx), 0, nrec, 0x00020000);
+      const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(lane_bcast(av_w, idx), 0, nrec, 0x00020000);
       kreg[cc] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rk, (int)t_off, 0, 0));
       vreg[cc] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rv, (int)t_off, 0, 0));
     }
   };
   const int k_lds = t_row * kKsStride + (tid & 15) * 8;
   const int v_lds = t_row * kVsStride + (tid & 15) * 8;
-  auto store_tile = [&](int kt) __attribute__((always_inline)) {
+  auto store_tile = [&](int kt, const u32x4 (&kreg)[4], const u32x4 (&vreg)[4]) __attribute__((always_inline)) {
     __bf16* kd = Ks + ((kt - t0) % kStages) * (kBN * kKsStride) + k_lds;
     __bf16* vd = Vs + ((kt - t0) % kStages) * (kBN * kVsStride) + v_lds;
 #pragma unroll
@@ -193,17 +195,35 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attn_kernel(DecParams p) {
     }
   };
 
-  // ---- main loop: the loads of tile kt+1 are in flight during the math on tile kt; one barrier per tile
-  load_tile(t0);
-  store_tile(t0);
+  // ---- main loop: while tile kt is computed, tile kt+1 sits in one register set (on its way to LDS) and the
+  // loads of tile kt+2 are in flight into the other; one barrier per tile.  Window w covers tiles
+  // t0 + 16 w .. + 15; the window of tile kt+2 is fetched one iteration before that tile is requested.
+  int cur_w = 0;
+  auto window_of = [&](int kt, uint64_t& ak, uint64_t& av) __attribute__((always_inline)) {
+    const bool nxt = ((kt - t0) >> 4) != cur_w;
+    ak = nxt ? ak_nxt : ak_cur;
+    av = nxt ? av_nxt : av_cur;
+  };
+  uint64_t akw, avw;
+  load_tile(t0, kregA, vregA, ak_cur, av_cur);
+  if (t0 + 1 < t1) load_tile(t0 + 1, kregB, vregB, ak_cur, av_cur);   // tile t0+1 is in window 0 (16 tiles per window)
+  store_tile(t0, kregA, vregA);
   __syncthreads();
-  for (int kt = t0; kt < t1; ++kt) {
-    if (((kt - t0 + 1) & 15) == 0) { ak_cur = ak_nxt; av_cur = av_nxt; }
-    if (((kt - t0 + 2) & 15) == 0) fetch_window((kt - t0 + 2) >> 4, ak_nxt, av_nxt);  // before the tile's loads: its wait sees only its own load
-    if (kt + 1 < t1) load_tile(kt + 1);
+  auto step = [&](int kt, u32x4 (&k_next)[4], u32x4 (&v_next)[4], u32x4 (&k_far)[4], u32x4 (&v_far)[4]) __attribute__((always_inline)) {
+    // k_next holds tile kt+1 (requested one step ago); k_far is free and takes tile kt+2
+    if (((kt - t0) >> 4) != cur_w) { cur_w = (kt - t0) >> 4; ak_cur = ak_nxt; av_cur = av_nxt; }
+    if (((kt - t0 + 3) & 15) == 0 && kt + 3 < t1) fetch_window((kt - t0 + 3) >> 4, ak_nxt, av_nxt);
+    if (kt + 2 < t1) {
+      window_of(kt + 2, akw, avw);
+      load_tile(kt + 2, k_far, v_far, akw, avw);
+    }
     compute(kt);
-    if (kt + 1 < t1) store_tile(kt + 1);
+    if (kt + 1 < t1) store_tile(kt + 1, k_next, v_next);
     __syncthreads();
+  };
+  for (int kt = t0; kt < t1; kt += 2) {
+    step(kt, kregB, vregB, kregA, vregA);
+    if (kt + 1 < t1) step(kt + 1, kregA, vregA, kregB, vregB);
   }
 
   // ---- merge the four wavefronts' states through LDS (the tiles are no longer needed after the last barrier)
@@ -290,11 +310,12 @@ int check_decode(const skv_attn_desc* d) {
   return SKV_OK;
 }
 
-// Key splits: enough workgroups to keep every CU's two slots busy several times over.
+// Key splits: about 4096 workgroups, i.e. eight rounds over the 512 workgroup slots of the chip (finer splits
+// shorten the tail when contexts differ in length; coarser ones amortise the start-up of a workgroup).
 void split_plan(const skv_attn_desc* d, int32_t n_req, int32_t max_blocks, int* n_splits, int* tiles_per_split) {
   const int64_t max_tiles = ((int64_t)max_blocks * SKV_BLOCK_TOKENS + kBN - 1) / kBN;
   const int64_t units = (int64_t)n_req * d->n_kv_heads;
-  int64_t want = units > 0 ? (2048 + units - 1) / units : 1;
+  int64_t want = units > 0 ? (4096 + units - 1) / units : 1;
   if (want > max_tiles) want = max_tiles;
   if (want < 1) want = 1;
   const int64_t tps = max_tiles > 0 ? (max_tiles + want - 1) / want : 1;
