@@ -50,7 +50,7 @@ def lib():
         _lib.okv_block_state.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.okv_insert_requests.restype = C.c_int64
         _lib.okv_insert_requests.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 5 + [C.c_int32, C.c_int64,
-                                                                                        C.c_void_p, C.c_void_p]
+                                                                                        C.c_void_p, C.c_void_p, C.c_int32]
         _lib.okv_set_epoch.argtypes = [C.c_void_p, C.c_uint32]
         _lib.okv_block_epochs.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
         _lib.okv_evict.restype = C.c_int64
@@ -138,9 +138,10 @@ class OracleTree:
         return int(self._l.okv_window_roll(self._t, int(direction), int(tau[0]), int(tau[1]), int(min_hits),
                                            int(n_consec), int(u_pre_max)))
 
-    def insert(self, req_off, req_tokens, req_tenant, matched_len, new_pages):
-        """Append the blocks the tree does not hold yet, private to the requesting tenant.  Returns
-        (first_inserted, n_inserted) per request; new entries take the ids n_in_blocks, n_in_blocks+1, ..."""
+    def insert(self, req_off, req_tokens, req_tenant, matched_len, new_pages, private_copies=False):
+        """Append the blocks the tree does not hold yet (private_copies: the blocks the requester cannot see),
+        private to the requesting tenant.  Returns (first_inserted, n_inserted) per request; new entries take
+        the ids n_in_blocks, n_in_blocks+1, ..."""
         req_off, req_tokens, req_tenant = _i32(req_off), _i32(req_tokens), _i32(req_tenant)
         matched_len, new_pages = _i32(matched_len), _i32(new_pages)
         R = len(req_tenant)
@@ -149,7 +150,7 @@ class OracleTree:
         n = np.zeros(R, dtype=np.int32)
         self.n_in_blocks = int(self._l.okv_insert_requests(
             self._t, R, _p(req_off), _p(req_tokens), _p(req_tenant), _p(matched_len), _p(new_pages),
-            new_pages.shape[1], self.n_in_blocks, _p(first), _p(n)))
+            new_pages.shape[1], self.n_in_blocks, _p(first), _p(n), int(private_copies)))
         return first, n
 
     def set_epoch(self, epoch):

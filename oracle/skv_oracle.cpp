@@ -66,7 +66,9 @@ struct BlockEntry {
 
 struct Node {
   std::vector<BlockEntry> blocks;               // the compressed edge: one or more blocks
-  std::map<BlockKey, std::unique_ptr<Node>> children;  // keyed by the child's whole first block
+  // keyed by the child's whole first block; several children may share a key (copies of the same content
+  // that different tenants created while they could not see each other's), kept in creation order
+  std::multimap<BlockKey, std::unique_ptr<Node>> children;
 };
 
 struct Tree {
@@ -90,7 +92,7 @@ void split_node(Node* node, size_t keep) {
   node->children.clear();
   node->blocks.resize(keep);
   BlockKey k = tail->blocks[0].tokens;
-  node->children[k] = std::move(tail);
+  node->children.emplace(k, std::move(tail));
 }
 
 void insert_sequence(Tree* t, const int32_t* tok, int64_t n_blocks, const uint8_t* sens,
@@ -99,8 +101,8 @@ void insert_sequence(Tree* t, const int32_t* tok, int64_t n_blocks, const uint8_
   int64_t j = 0;  // next block of the sequence
   while (j < n_blocks) {
     BlockKey k = key_at(tok + j * kBlock);
-    auto it = node->children.find(k);
-    if (it == node->children.end()) {
+    auto it = node->children.lower_bound(k);   // one copy per block-prefix in this mode: the oldest child with this key
+    if (it == node->children.end() || !(it->first == k)) {
       // nothing cached below this point: append the remainder as new entries
       Node* at = node;
       while (j < n_blocks) {
@@ -120,7 +122,7 @@ void insert_sequence(Tree* t, const int32_t* tok, int64_t n_blocks, const uint8_
         }
         BlockKey fk = fresh->blocks[0].tokens;
         Node* next = fresh.get();
-        at->children[fk] = std::move(fresh);
+        at->children.emplace(fk, std::move(fresh));
         at = next;
       }
       return;
@@ -140,27 +142,62 @@ void insert_sequence(Tree* t, const int32_t* tok, int64_t n_blocks, const uint8_
   }
 }
 
-// Longest visible prefix for one request.  Returns matched blocks; fills entries.
-int64_t match_one(Tree* t, const int32_t* tok, int64_t n_tokens, int32_t tenant,
-                  std::vector<BlockEntry*>* out) {
-  const int64_t nb = n_tokens / kBlock;  // a trailing partial block never matches
-  Node* node = &t->root;
-  int64_t j = 0;
-  while (j < nb) {
-    auto it = node->children.find(key_at(tok + j * kBlock));
-    if (it == node->children.end()) return j;
-    Node* child = it->second.get();
-    for (size_t i = 0; i < child->blocks.size(); ++i) {
-      if (j == nb) return j;
-      BlockEntry& e = child->blocks[i];
-      if (!(e.tokens == key_at(tok + j * kBlock))) return j;
-      if (e.is_private && e.creator_id != tenant) return j;   // visibility rule, every hop
-      out->push_back(&e);
-      ++j;
+// Longest visible prefix for one request (Section 4.3.1 Search: the visibility rule is checked at every
+// hop and the walk stops at the first entry the requester may not use).  Where several children start with
+// the request's next block -- copies of the same content, Section 4.1: selective isolation leaves redundant
+// copies -- every copy whose first block is visible is followed and the longest result kept; among equally
+// long results the one found first wins, copies being tried in creation order (ascending block id).
+struct PathEnd { Node* node; size_t used; };  // where a path stops: `used` blocks of `node` belong to it
+
+struct Search {
+  const int32_t* tok;
+  int64_t nb;
+  int32_t tenant;
+  std::vector<BlockEntry*> cur, best;
+  PathEnd best_end;
+  bool have = false;
+
+  void consider(Node* node, size_t used) {
+    if (!have || cur.size() > best.size()) {
+      best = cur;
+      best_end = PathEnd{node, used};
+      have = true;
     }
-    node = child;
   }
-  return j;
+  // `node` is fully matched (or the root); the request's next block is j
+  void descend(Node* node, int64_t j) {
+    bool went = false;
+    if (j < nb) {
+      auto range = node->children.equal_range(key_at(tok + j * kBlock));
+      for (auto it = range.first; it != range.second; ++it) {
+        Node* child = it->second.get();
+        size_t m = 0;  // leading blocks of the child's edge that match and are visible
+        while (m < child->blocks.size() && j + (int64_t)m < nb) {
+          BlockEntry& e = child->blocks[m];
+          if (!(e.tokens == key_at(tok + (j + m) * kBlock))) break;
+          if (e.is_private && e.creator_id != tenant) break;   // visibility rule, every hop
+          ++m;
+        }
+        if (m == 0) continue;
+        went = true;
+        for (size_t i = 0; i < m; ++i) cur.push_back(&child->blocks[i]);
+        if (m == child->blocks.size()) descend(child, j + (int64_t)m);
+        else consider(child, m);
+        cur.resize(cur.size() - m);
+        if ((int64_t)best.size() == nb) return;   // cannot get longer
+      }
+    }
+    if (!went) consider(node, node->blocks.size());
+  }
+};
+
+int64_t match_one(Tree* t, const int32_t* tok, int64_t n_tokens, int32_t tenant,
+                  std::vector<BlockEntry*>* out, PathEnd* end = nullptr) {
+  Search s{tok, n_tokens / kBlock, tenant, {}, {}, PathEnd{&t->root, 0}};  // a trailing partial block never matches
+  s.descend(&t->root, 0);
+  *out = s.best;
+  if (end) *end = s.best_end;
+  return (int64_t)s.best.size();
 }
 
 void for_each_block(Node* n, const std::function<void(BlockEntry&)>& f) {
@@ -265,8 +302,9 @@ int64_t existing_prefix_blocks(Tree* t, const int32_t* tok, int64_t n_blocks) {
   Node* node = &t->root;
   int64_t j = 0;
   while (j < n_blocks) {
-    auto it = node->children.find(key_at(tok + j * kBlock));
-    if (it == node->children.end()) return j;
+    const BlockKey k = key_at(tok + j * kBlock);
+    auto it = node->children.lower_bound(k);
+    if (it == node->children.end() || !(it->first == k)) return j;
     Node* child = it->second.get();
     for (size_t i = 0; i < child->blocks.size(); ++i) {
       if (j == n_blocks || !(child->blocks[i].tokens == key_at(tok + j * kBlock))) return j;
@@ -285,10 +323,15 @@ int64_t existing_prefix_blocks(Tree* t, const int32_t* tok, int64_t n_blocks) {
 // a page (< 0 or beyond max_new_blocks).  New entries get the ids next_block_id, next_block_id+1, ... in
 // request order.  Per request: first_inserted = index of its first new block, n_inserted = how many.
 // Returns the next free block id.
+//
+// private_copies != 0 (Section 4.1: selective isolation leaves redundant copies): a requester that is stopped
+// by an entry it may not see adds its own copy instead.  The request's longest visible path is looked up in
+// the tree as it stands (requests are handled in order), and all of its full blocks beyond that path are
+// appended below the path's end, private to the tenant -- next to whatever other tenants cached there.
 int64_t okv_insert_requests(void* tp, int32_t n_req, const int32_t* req_off, const int32_t* req_tokens,
                             const int32_t* req_tenant, const int32_t* matched_len, const int32_t* new_pages,
                             int32_t max_new_blocks, int64_t next_block_id, int32_t* first_inserted,
-                            int32_t* n_inserted) {
+                            int32_t* n_inserted, int32_t private_copies) {
   Tree* t = (Tree*)tp;
   for (int32_t r = 0; r < n_req; ++r) {
     const int32_t* tok = req_tokens + req_off[r];
@@ -297,6 +340,31 @@ int64_t okv_insert_requests(void* tp, int32_t n_req, const int32_t* req_off, con
     int64_t have = 0;  // leading suffix blocks that come with a page
     while (have < max_new_blocks && new_pages[(int64_t)r * max_new_blocks + have] >= 0) ++have;
     if (nb > k_vis + have) nb = k_vis + have;
+    if (private_copies) {
+      std::vector<BlockEntry*> path;
+      PathEnd end{&t->root, 0};
+      const int64_t k = match_one(t, tok, nb * kBlock, req_tenant[r], &path, &end);
+      first_inserted[r] = (int32_t)k;
+      n_inserted[r] = 0;
+      if (k >= nb || k < k_vis) continue;
+      if (end.used < end.node->blocks.size()) split_node(end.node, end.used);  // the path stops inside a compressed edge
+      auto fresh = std::make_unique<Node>();
+      for (int64_t j = k; j < nb; ++j) {
+        BlockEntry e;
+        e.tokens = key_at(tok + j * kBlock);
+        e.is_private = true;
+        e.creator_id = req_tenant[r];
+        e.page_id = new_pages[(int64_t)r * max_new_blocks + (j - k_vis)];
+        e.block_id = next_block_id++;
+        e.epoch = t->epoch;
+        fresh->blocks.push_back(e);
+        t->n_blocks++;
+      }
+      const BlockKey fk = fresh->blocks[0].tokens;
+      end.node->children.emplace(fk, std::move(fresh));
+      n_inserted[r] = (int32_t)(nb - k);
+      continue;
+    }
     const int64_t k_exist = existing_prefix_blocks(t, tok, nb);
     first_inserted[r] = (int32_t)k_exist;
     n_inserted[r] = 0;
@@ -358,7 +426,11 @@ int64_t okv_evict(void* tp, int64_t n_want, int64_t n_protect, const int64_t* pr
     ++done;
     v.node->blocks.pop_back();
     t->n_blocks--;
-    if (v.node->blocks.empty()) v.parent->children.erase(gone.tokens);  // it was the node's first block
+    if (v.node->blocks.empty()) {  // it was the node's first block: the node leaves its parent
+      auto range = v.parent->children.equal_range(gone.tokens);
+      for (auto it = range.first; it != range.second; ++it)
+        if (it->second.get() == v.node) { v.parent->children.erase(it); break; }
+    }
   }
   return done;
 }
