@@ -100,7 +100,17 @@ int skv_tree_build(const skv_tree_desc* desc, void* d_slab, size_t bytes, void* 
  * beyond the cached path.  new_pages[r*max_new_blocks + j] is the pool page of the request's block
  * matched_len[r]/16 + j (the table skv_scatter_kv wrote through; matched_len as skv_match returned it);
  * insertion stops at the first block without a page (< 0, or j >= max_new_blocks).  Requests are inserted
- * in order, so a later request of the batch finds what an earlier one added.  New entries receive the input
+ * in order, so a later request of the batch finds what an earlier one added.
+ * private_copies != 0 (Section 4.1: selective isolation leaves redundant copies): a requester stopped by an
+ * entry it may not see adds its own copy.  The request's longest visible path is looked up in the tree as
+ * it stands, and all full blocks beyond that path are appended below its end, private to the tenant, next
+ * to whatever other tenants cached there.  A position may then hold several children that start with the
+ * same block; from the first such insertion on skv_match follows every copy whose first block the tenant
+ * may see and returns the longest path (equally long ones: the path through the copy with the smaller
+ * input block id at the first difference).  Its search explores at most 10 such branch points per request
+ * exhaustively, 64 copies per position and 4096 root-to-end walks; beyond those limits the oldest visible
+ * copy is taken.  This mode reads the visibility bits back from the device first.
+ * New entries receive the input
  * block ids n_in_blocks, n_in_blocks + 1, ... in that order, start with zeroed counters, and are visible to
  * skv_match calls enqueued afterwards.  first_inserted[r] / n_inserted[r] report the index of the request's
  * first new block and their number (pages given for blocks below first_inserted[r] stay unused).
@@ -111,7 +121,8 @@ int skv_tree_build(const skv_tree_desc* desc, void* d_slab, size_t bytes, void* 
  * overlap with other calls on the tree. */
 int skv_tree_insert(skv_tree* tree, int32_t n_req, const int32_t* req_off, const int32_t* req_tokens,
                     const int32_t* req_tenant, const int32_t* matched_len, const int32_t* new_pages,
-                    int32_t max_new_blocks, int32_t* first_inserted, int32_t* n_inserted, void* stream);
+                    int32_t max_new_blocks, int32_t private_copies, int32_t* first_inserted,
+                    int32_t* n_inserted, void* stream);
 
 /* Global epoch counter (Section 4.3.2: the index keeps a global epoch_counter and every entry its most
  * recent access epoch).  skv_match calls enqueued after this call stamp `epoch` on every block they match;

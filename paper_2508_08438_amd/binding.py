@@ -79,7 +79,7 @@ def lib():
         l.skv_block_epochs_read.argtypes = [vp, vp, vp]
         l.skv_evict.argtypes = [vp, C.c_int64, vp, C.c_int64, vp, vp, C.POINTER(C.c_int64), vp]
         l.skv_tree_size_for_capacity.argtypes = [C.c_int64, C.POINTER(C.c_size_t)]
-        l.skv_tree_insert.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+        l.skv_tree_insert.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
         l.skv_scatter_kv.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, vp, vp, i32, vp, vp, i32, vp]
         l.skv_suffix_offsets.argtypes = [i32, vp, vp, vp, vp]
         l.skv_gather_kv.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, i32, vp, vp, i32, vp, vp, vp, i64, vp]
@@ -171,7 +171,8 @@ def skv_tree_build(seq_tokens, seq_off, blk_sensitive, blk_owner, blk_page, n_te
     return Tree(h, slab)
 
 
-def skv_tree_insert(tree: Tree, req_off, req_tokens, req_tenant, matched_len, new_pages, stream=None):
+def skv_tree_insert(tree: Tree, req_off, req_tokens, req_tenant, matched_len, new_pages, private_copies=False,
+                    stream=None):
     """Host arrays in (numpy int32), per-request (first_inserted, n_inserted) out."""
     a = [np.ascontiguousarray(x, dtype=np.int32) for x in (req_off, req_tokens, req_tenant, matched_len, new_pages)]
     n_req = len(a[2])
@@ -181,7 +182,8 @@ def skv_tree_insert(tree: Tree, req_off, req_tokens, req_tenant, matched_len, ne
     hp = lambda x: C.c_void_p(x.ctypes.data) if x.size else None
     with torch.cuda.device(tree.slab.device):
         _check(lib().skv_tree_insert(tree.handle, n_req, hp(a[0]), hp(a[1]), hp(a[2]), hp(a[3]), hp(a[4]),
-                                     a[4].shape[1], hp(first), hp(n), _stream(stream)), "skv_tree_insert")
+                                     a[4].shape[1], int(private_copies), hp(first), hp(n), _stream(stream)),
+               "skv_tree_insert")
     return first, n
 
 

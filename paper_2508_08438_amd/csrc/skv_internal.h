@@ -47,6 +47,7 @@ struct skv_tree {
   int64_t n_in_blocks;
   int device;
   SkvHostMirror* host;
+  int has_copies;  // some position holds several children with the same first block: lookups must branch
 };
 
 // ---- block hash (host builds the tables, device probes them) -------------------------------

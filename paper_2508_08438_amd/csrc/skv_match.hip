@@ -139,6 +139,167 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
   for (int i = j + lane; i < max_blocks; i += kWave) row[i] = -1;
 }
 
+// ---- lookup on a tree with per-tenant copies ---------------------------------------------------------
+// (Section 4.1: selective isolation leaves redundant copies of the same content.)  A position may then hold
+// several children that start with the request's next block, and the longest visible path can run through
+// any copy whose first block the tenant may see.  One wavefront still owns a request; it walks the tree
+// once per combination of choices, in lexicographic order of the choices (copies ordered by the input block
+// id of their first block), and keeps the first of the longest walks -- the order in which a depth-first
+// search that tries older copies first meets them.  A walk is described by up to kMaxChoice 6-bit ranks
+// packed into one 64-bit word; past that many branch points, or past kMaxCopies copies at one position, the
+// oldest visible copy is taken without alternatives, and at most kMaxWalks walks are made.
+constexpr int kMaxChoice = 10;
+constexpr int kMaxCopies = 64;
+constexpr int kMaxWalks = 4096;
+
+// The `want`-th oldest child of `nd` whose first block equals the request block at x and is visible to the
+// tenant; *n_out = how many such children there are.  -1 if none.
+__device__ inline int find_child_ranked(const SkvTreeDev& t, const SkvNode nd, const int32_t* x, int tenant, int lane,
+                                        int want, int* n_out) {
+  *n_out = 0;
+  if (nd.tab_cap == 0) return -1;
+  const uint64_t h = hash_block(x, lane);
+  const uint32_t mask = (uint32_t)nd.tab_cap - 1u;
+  int n = 0;                       // candidates so far (uniform); candidate i lives in lane i
+  int my_canon = 0x7fffffff, my_child = -1;
+  for (int base = 0; base < nd.tab_cap; base += kWave) {
+    const bool valid = base + lane < nd.tab_cap;
+    SkvSlot e{0, 0, -1, 0};
+    if (valid) e = t.slots[nd.tab_off + (((uint32_t)h + (uint32_t)(base + lane)) & mask)];
+    const uint64_t empty = ballot64(valid && e.child == -1);
+    uint64_t cand = ballot64(valid && e.child >= 0 && e.hash_lo == (uint32_t)h && e.hash_hi == (uint32_t)(h >> 32));
+    if (empty) cand &= (empty & (~empty + 1)) - 1;
+    while (cand) {
+      const int l = __builtin_ctzll(cand);
+      const int child = __shfl(e.child, l);
+      const int cfirst = uniform(t.nodes[child].first);
+      if (block_equal(x, t.tok + (size_t)cfirst * 16, lane)) {
+        const int m = uniform(t.meta[cfirst]);
+        const bool visible = !(m < 0 && (m & 0x7fffffff) != tenant);
+        if (visible && n < kMaxCopies) {
+          const int id = uniform(t.canon[cfirst]);
+          if (lane == n) { my_canon = id; my_child = child; }
+          ++n;
+        }
+      }
+      cand &= cand - 1;
+    }
+    if (empty) break;
+  }
+  *n_out = n;
+  if (n == 0) return -1;
+  int rank = 0;                    // how many candidates are older than this lane's
+  for (int i = 0; i < n; ++i) rank += __shfl(my_canon, i) < my_canon ? 1 : 0;
+  if (want >= n) want = 0;
+  const uint64_t sel = ballot64(lane < n && rank == want);
+  return __shfl(my_child, __builtin_ctzll(sel));
+}
+
+__global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_copies_kernel(
+    SkvTreeDev t, int n_req, const int32_t* __restrict__ req_off, const int32_t* __restrict__ req_tok,
+    const int32_t* __restrict__ req_tenant, int max_blocks, int32_t* __restrict__ matched_len,
+    int32_t* __restrict__ page_table) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int r = blockIdx.x * kWavesPerWg + (threadIdx.x >> 6);
+  if (r >= n_req) return;
+  const int lo = uniform(req_off[r]), hi = uniform(req_off[r + 1]);
+  const int tenant = uniform(req_tenant[r]);
+  int nb = hi > lo ? (hi - lo) / SKV_BLOCK_TOKENS : 0;
+  if (nb > max_blocks) nb = max_blocks;
+  if (tenant < 0 || tenant >= t.n_tenants) nb = 0;
+  const int32_t* x = req_tok + lo;
+  int32_t* row = page_table + (size_t)r * max_blocks;   // holds block records during the walks, page ids at the end
+
+  // One walk under the choices `ranks`: writes the matched blocks' record indices to row[], returns their
+  // number; *n_choice / *counts describe the branch points met (how many visible copies each had).
+  auto walk = [&](uint64_t ranks, int* n_choice, uint64_t* counts) {
+    int j = 0, node = 0, dp = 0;
+    uint64_t cnt = 0;
+    bool stop = false;
+    while (j < nb && !stop) {
+      SkvNode cur = t.nodes[node];
+      cur.tab_off = uniform(cur.tab_off);
+      cur.tab_cap = uniform(cur.tab_cap);
+      int n = 0;
+      const int want = dp < kMaxChoice ? (int)((ranks >> (6 * dp)) & 63) : 0;
+      const int child = find_child_ranked(t, cur, x + (size_t)j * 16, tenant, lane, want, &n);
+      if (child < 0) break;
+      if (n >= 2 && dp < kMaxChoice) {
+        cnt |= (uint64_t)(n - 1) << (6 * dp);   // highest rank at this branch point
+        ++dp;
+      }
+      SkvNode nd = t.nodes[child];
+      const int first = uniform(nd.first);
+      const int nblk = uniform(nd.n_blocks);
+      const int span = min(nblk, nb - j);
+      for (int c = 0; c < span && !stop; c += kStepBlocks) {
+        const int cb = min(kStepBlocks, span - c);
+        const int ntok = cb * 16;
+        const int32_t* tt = t.tok + (size_t)(first + c) * 16;
+        const int32_t* xx = x + (size_t)j * 16;
+        int32_t a[kSub], b[kSub];
+#pragma unroll
+        for (int u = 0; u < kSub; ++u) {
+          const int i = u * kWave + lane;
+          a[u] = i < ntok ? xx[i] : 0;
+          b[u] = i < ntok ? tt[i] : 0;
+        }
+        const int m = lane < cb ? t.meta[first + c + lane] : 0;
+        int n_eq = cb;
+#pragma unroll
+        for (int u = kSub - 1; u >= 0; --u) {
+          const uint64_t ne = ballot64(a[u] != b[u]);
+          if (ne) n_eq = u * 4 + (__builtin_ctzll(ne) >> 4);
+        }
+        const uint64_t hidden = ballot64(m < 0 && (m & 0x7fffffff) != tenant);
+        const int n_vis = hidden ? __builtin_ctzll(hidden) : cb;
+        const int take = min(n_eq, n_vis);
+        if (lane < take) row[j + lane] = first + c + lane;
+        j += take;
+        if (take < cb) stop = true;
+      }
+      node = child;
+    }
+    *n_choice = dp;
+    *counts = cnt;
+    return j;
+  };
+
+  uint64_t ranks = 0, best_ranks = 0;
+  int best = -1;
+  for (int walks = 0; walks < kMaxWalks; ++walks) {
+    int dp = 0;
+    uint64_t top = 0;
+    const int len = walk(ranks, &dp, &top);
+    if (len > best) { best = len; best_ranks = ranks; }
+    if (len == nb) break;
+    int i = dp - 1;   // deepest branch point that still has an untried copy
+    while (i >= 0 && ((ranks >> (6 * i)) & 63) >= ((top >> (6 * i)) & 63)) --i;
+    if (i < 0) break;
+    const uint64_t keep = ((uint64_t)1 << (6 * i)) - 1;
+    ranks = (ranks & keep) | ((((ranks >> (6 * i)) & 63) + 1) << (6 * i));
+  }
+  if (best < 0) best = 0;
+  if (ranks != best_ranks) {   // row[] holds another walk: redo the chosen one
+    int dp;
+    uint64_t top;
+    walk(best_ranks, &dp, &top);
+  }
+  __threadfence();   // row[] was written by other lanes of this wavefront: make the stores visible to the loads below
+  const uint32_t tbit = 1u << (tenant & 31);
+  const int tword = 1 + (tenant >> 5);
+  for (int i = lane; i < best; i += kWave) {
+    const int blk = row[i];
+    row[i] = t.page[blk];
+    uint32_t* ctr = t.ctr + (size_t)blk * SKV_CTR_STRIDE;
+    atomicAdd(ctr, 1u);
+    atomicOr(ctr + tword, tbit);
+    t.epoch[blk] = t.cur_epoch;
+  }
+  if (lane == 0) matched_len[r] = best * SKV_BLOCK_TOKENS;
+  for (int i = best + lane; i < max_blocks; i += kWave) row[i] = -1;
+}
+
 __global__ void skv_suffix_offsets_kernel(int n_req, const int32_t* __restrict__ req_off,
                                           const int32_t* __restrict__ matched_len,
                                           int32_t* __restrict__ q_off) {
@@ -179,8 +340,12 @@ extern "C" int skv_match(skv_tree* t, int32_t n_req, const int32_t* d_req_off,
   if (!d_req_off || !d_req_tokens || !d_req_tenant || !d_matched_len) return SKV_EINVAL;
   if (max_blocks > 0 && !d_page_table) return SKV_EINVAL;
   const int grid = (n_req + kWavesPerWg - 1) / kWavesPerWg;
-  skv_match_kernel<<<grid, kWave * kWavesPerWg, 0, (hipStream_t)stream>>>(
-      t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table);
+  if (t->has_copies)
+    skv_match_copies_kernel<<<grid, kWave * kWavesPerWg, 0, (hipStream_t)stream>>>(
+        t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table);
+  else
+    skv_match_kernel<<<grid, kWave * kWavesPerWg, 0, (hipStream_t)stream>>>(
+        t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table);
   SKV_HIP(hipGetLastError());
   return SKV_OK;
 }

@@ -345,6 +345,7 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   SkvHostMirror* m = new (std::nothrow) SkvHostMirror();
   if (!m) { delete t; return SKV_EINVAL; }
   t->host = m;
+  t->has_copies = 0;
   m->L = L;
   m->base = base;
   m->cap_blocks = cap_blocks;
@@ -458,6 +459,116 @@ struct Inserter {
     m->kids[node] = kids;
     return true;
   }
+  // ---- private copies: the requester's longest visible path, depth first, older copies first ----
+  std::vector<int32_t> vis_meta;   // visibility word of every block record (read back, then extended)
+  bool track_vis = false;
+  const int32_t* sx = nullptr;
+  int64_t snb = 0, cur_len = 0, best_len = 0;
+  int32_t stenant = 0, best_node = 0, best_used = 0;
+  bool have_best = false;
+  void consider(int32_t node, int32_t used) {
+    if (!have_best || cur_len > best_len) { best_len = cur_len; best_node = node; best_used = used; have_best = true; }
+  }
+  void descend(int32_t node, int64_t j) {
+    bool went = false;
+    const SkvNode n = m->nodes[node];
+    if (j < snb && n.tab_cap) {
+      const uint64_t h = skv_hash_block_host(sx + j * 16);
+      std::vector<std::pair<int32_t, int32_t>> cands;  // (input id of the first block, child)
+      for (uint32_t s = (uint32_t)h & (uint32_t)(n.tab_cap - 1);; s = (s + 1) & (uint32_t)(n.tab_cap - 1)) {
+        const SkvSlot& sl = m->slots[(size_t)n.tab_off + s];
+        if (sl.child == -1) break;
+        if (sl.child >= 0 && sl.hash_lo == (uint32_t)h && sl.hash_hi == (uint32_t)(h >> 32) &&
+            !memcmp(&m->tok[(size_t)m->nodes[sl.child].first * 16], sx + j * 16, 64))
+          cands.push_back({m->canon[m->nodes[sl.child].first], sl.child});
+      }
+      std::sort(cands.begin(), cands.end());
+      for (const auto& cd : cands) {
+        const SkvNode c = m->nodes[cd.second];
+        int64_t k = 0;
+        while (k < c.n_blocks && j + k < snb) {
+          if (memcmp(&m->tok[((size_t)c.first + k) * 16], sx + (j + k) * 16, 64)) break;
+          const int32_t mt = vis_meta[(size_t)c.first + k];
+          if (mt < 0 && (mt & 0x7fffffff) != stenant) break;
+          ++k;
+        }
+        if (k == 0) continue;
+        went = true;
+        cur_len += k;
+        if (k == c.n_blocks) descend(cd.second, j + k);
+        else consider(cd.second, (int32_t)k);
+        cur_len -= k;
+        if (best_len == snb) return;
+      }
+    }
+    if (!went) consider(node, n.n_blocks);
+  }
+  // Appends blocks [k, nb) of the request below the end of its own longest visible path.  Returns k, or -1
+  // when the slab is full.
+  int64_t insert_copy(const int32_t* x, int64_t nb, int32_t tenant, const int32_t* pages, int64_t k_vis, int64_t* n_new) {
+    *n_new = 0;
+    sx = x; snb = nb; stenant = tenant; cur_len = 0; best_len = 0; best_node = 0; best_used = 0; have_best = false;
+    descend(0, 0);
+    const int64_t k = best_len;
+    if (k >= nb || k < k_vis) return k;
+    int32_t at = best_node;
+    const SkvNode run = m->nodes[at];
+    if (best_used < run.n_blocks) {  // the path stops inside a compressed edge: split it there
+      if ((int64_t)m->nodes.size() + 2 > m->cap_blocks + 1) return -1;
+      if (!split(at, best_used)) return -1;
+    }
+    const int64_t add = nb - k;
+    if (n_blocks + add > m->cap_blocks || n_in + add > m->cap_blocks) return -1;
+    if ((int64_t)m->nodes.size() + 1 > m->cap_blocks + 1) return -1;
+    return append(at, x, k, nb, tenant, pages, k_vis, n_new) ? k : -1;
+  }
+  // Cuts node c after its first j blocks: a new node takes the rest together with the child table.
+  bool split(int32_t c, int64_t j) {
+    const SkvNode run = m->nodes[c];
+    const int32_t tail = (int32_t)m->nodes.size();
+    m->nodes.push_back(SkvNode{run.first + (int32_t)j, run.n_blocks - (int32_t)j, run.tab_off, run.tab_cap});
+    m->kids.push_back(m->kids[c]);
+    m->filled.push_back(m->filled[c]);
+    m->parent.push_back(c);
+    for (int32_t q = 0; q < run.tab_cap; ++q) {  // the children move below the new node
+      const int32_t gc = m->slots[(size_t)run.tab_off + q].child;
+      if (gc >= 0) m->parent[gc] = tail;
+    }
+    m->nodes[c].n_blocks = (int32_t)j;
+    m->nodes[c].tab_off = 0;
+    m->nodes[c].tab_cap = 0;
+    m->kids[c] = 0;
+    m->filled[c] = 0;
+    touch_node((size_t)c);
+    touch_node((size_t)tail);
+    return add_child(c, skv_hash_block_host(&m->tok[((size_t)run.first + j) * 16]), tail);
+  }
+  // New node with blocks [i, nb) of the request as a child of `node`.
+  bool append(int32_t node, const int32_t* x, int64_t i, int64_t nb, int32_t tenant, const int32_t* pages,
+              int64_t k_vis, int64_t* n_new) {
+    const int64_t add = nb - i;
+    const int32_t fresh = (int32_t)m->nodes.size();
+    m->nodes.push_back(SkvNode{(int32_t)n_blocks, (int32_t)add, 0, 0});
+    m->kids.push_back(0);
+    m->filled.push_back(0);
+    m->parent.push_back(node);
+    touch_node((size_t)fresh);
+    if (!add_child(node, skv_hash_block_host(x + i * 16), fresh)) return false;
+    m->tok.insert(m->tok.end(), x + i * 16, x + nb * 16);
+    for (int64_t j = i; j < nb; ++j) {
+      page.push_back(pages[j - k_vis]);
+      meta.push_back((int32_t)0x80000000 | tenant);
+      if (track_vis) vis_meta.push_back((int32_t)0x80000000 | tenant);
+      m->page.push_back(pages[j - k_vis]);
+      m->canon.push_back((int32_t)(n_in + (j - i)));
+      m->flat_of.push_back((int32_t)(n_blocks + (j - i)));
+      m->page_used[pages[j - k_vis]] = 1;
+    }
+    n_blocks += add;
+    n_in += add;
+    *n_new = add;
+    return true;
+  }
   // One request: blocks [k_exist, nb) are appended as one node below the point where the path ends.
   // Returns k_exist, or -1 when the slab is full.
   int64_t insert(const int32_t* x, int64_t nb, int32_t tenant, const int32_t* pages, int64_t k_vis, int64_t* n_new) {
@@ -476,23 +587,7 @@ struct Inserter {
         if (i + j < k_vis) return i + j;  // caller's matched length is not one this tree gives
         // split: the run keeps its first j blocks, a new node takes the rest together with the child table
         if ((int64_t)m->nodes.size() + 2 > m->cap_blocks + 1) return -1;
-        const int32_t tail = (int32_t)m->nodes.size();
-        m->nodes.push_back(SkvNode{run.first + (int32_t)j, run.n_blocks - (int32_t)j, run.tab_off, run.tab_cap});
-        m->kids.push_back(m->kids[c]);
-        m->filled.push_back(m->filled[c]);
-        m->parent.push_back(c);
-        for (int32_t q = 0; q < run.tab_cap; ++q) {  // the children move below the new node
-          const int32_t gc = m->slots[(size_t)run.tab_off + q].child;
-          if (gc >= 0) m->parent[gc] = tail;
-        }
-        m->nodes[c].n_blocks = (int32_t)j;
-        m->nodes[c].tab_off = 0;
-        m->nodes[c].tab_cap = 0;
-        m->kids[c] = 0;
-        m->filled[c] = 0;
-        touch_node((size_t)c);
-        touch_node((size_t)tail);
-        if (!add_child(c, skv_hash_block_host(&m->tok[((size_t)run.first + j) * 16]), tail)) return -1;
+        if (!split(c, j)) return -1;
         node = c;
         i += j;
         break;
@@ -503,25 +598,7 @@ struct Inserter {
     if (i >= nb || i < k_vis) return i;
     const int64_t add = nb - i;
     if (n_blocks + add > m->cap_blocks || n_in + add > m->cap_blocks) return -1;
-    const int32_t fresh = (int32_t)m->nodes.size();
-    m->nodes.push_back(SkvNode{(int32_t)n_blocks, (int32_t)add, 0, 0});
-    m->kids.push_back(0);
-    m->filled.push_back(0);
-    m->parent.push_back(node);
-    touch_node((size_t)fresh);
-    if (!add_child(node, skv_hash_block_host(x + i * 16), fresh)) return -1;
-    m->tok.insert(m->tok.end(), x + i * 16, x + nb * 16);
-    for (int64_t j = i; j < nb; ++j) {
-      page.push_back(pages[j - k_vis]);
-      meta.push_back((int32_t)0x80000000 | tenant);
-      m->page.push_back(pages[j - k_vis]);
-      m->canon.push_back((int32_t)(n_in + (j - i)));
-      m->flat_of.push_back((int32_t)(n_blocks + (j - i)));
-      m->page_used[pages[j - k_vis]] = 1;
-    }
-    n_blocks += add;
-    n_in += add;
-    *n_new = add;
+    if (!append(node, x, i, nb, tenant, pages, k_vis, n_new)) return -1;
     return i;
   }
 };
@@ -530,7 +607,8 @@ struct Inserter {
 
 extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_off, const int32_t* req_tokens,
                                const int32_t* req_tenant, const int32_t* matched_len, const int32_t* new_pages,
-                               int32_t max_new_blocks, int32_t* first_inserted, int32_t* n_inserted, void* stream) {
+                               int32_t max_new_blocks, int32_t private_copies, int32_t* first_inserted,
+                               int32_t* n_inserted, void* stream) {
   if (!t || !t->host || n_req < 0 || max_new_blocks < 0) return SKV_EINVAL;
   if (n_req == 0) return SKV_OK;
   if (!req_off || !req_tenant || !matched_len || !first_inserted || !n_inserted) return SKV_EINVAL;
@@ -562,14 +640,25 @@ extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_of
   const std::vector<int32_t> filled0 = m->filled, parent0 = m->parent;
   const size_t slots_used0 = m->slots_used, tok0 = m->tok.size(), blocks0 = m->canon.size(), in0 = m->flat_of.size();
   Inserter ins{t, m, t->dev.n_blocks, t->n_in_blocks, {}, {}, SIZE_MAX, 0, SIZE_MAX, 0};
+  hipStream_t st = (hipStream_t)stream;
+  if (private_copies) {  // the requester's own path depends on the visibility bits, which live on the device
+    ins.track_vis = true;
+    ins.vis_meta.resize((size_t)t->dev.n_blocks);
+    if (t->dev.n_blocks) {
+      SKV_HIP(hipMemcpyAsync(ins.vis_meta.data(), t->dev.meta, (size_t)t->dev.n_blocks * 4, hipMemcpyDeviceToHost, st));
+      SKV_HIP(hipStreamSynchronize(st));
+    }
+  }
   bool full = false;
   for (int32_t r = 0; r < n_req && !full; ++r) {
     const int64_t k_vis = matched_len[r] / SKV_BLOCK_TOKENS;
     int64_t nb = (req_off[r + 1] - req_off[r]) / SKV_BLOCK_TOKENS;
     if (nb > k_vis + have[r]) nb = k_vis + have[r];
     int64_t n_new = 0;
-    const int64_t first = ins.insert(req_tokens + req_off[r], nb, req_tenant[r],
-                                     new_pages + (size_t)r * max_new_blocks, k_vis, &n_new);
+    const int32_t* pages_r = new_pages + (size_t)r * max_new_blocks;
+    const int64_t first = private_copies
+                              ? ins.insert_copy(req_tokens + req_off[r], nb, req_tenant[r], pages_r, k_vis, &n_new)
+                              : ins.insert(req_tokens + req_off[r], nb, req_tenant[r], pages_r, k_vis, &n_new);
     if (first < 0) { full = true; break; }
     first_inserted[r] = (int32_t)first;
     n_inserted[r] = (int32_t)n_new;
@@ -583,8 +672,8 @@ extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_of
   }
   // upload: the appended block records, then the spans of node and slot records that changed
   const int64_t nb0 = t->dev.n_blocks, nin0 = t->n_in_blocks, add = ins.n_blocks - nb0;
-  hipStream_t st = (hipStream_t)stream;
   char* base = m->base;
+  if (private_copies && add > 0) t->has_copies = 1;
   if (add > 0) {
     std::vector<int32_t> canon((size_t)add), flat_of((size_t)add);
     for (int64_t i = 0; i < add; ++i) { canon[i] = (int32_t)(nin0 + i); flat_of[i] = (int32_t)(nb0 + i); }

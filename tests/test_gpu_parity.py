@@ -784,3 +784,138 @@ def test_evict_config3_then_reinsert():
     o_ml4, o_pt4 = otree.match(w.req_off, w.req_tokens, w.req_tenant, mb)
     assert np.array_equal(ml4, o_ml4) and np.array_equal(pt4, o_pt4)
     compare_state(skv, dtree, otree, "c3")
+
+
+# ---------------------------------------------------------------------------------------------
+# per-tenant copies of the same content (Section 4.1): insert below the requester's own path, branching lookup
+
+def run_copy_stream(seed, n_rounds=5, n_req=10):
+    from test_oracle_insert import make_round
+    skv = _skv()
+    block_vocab = 3 if seed % 3 == 0 else None
+    w = inputs.small_random(seed=seed, n_req=8, p_sens=0.4, n_tenants=3, block_vocab=block_vocab)
+    vocab = int(w.seq_tokens.max()) + 1 if len(w.seq_tokens) else 2
+    otree = oracle.OracleTree.from_workload(w)
+    dtree = skv.skv_tree_build(w.seq_tokens, w.seq_off, w.blk_sensitive, w.blk_owner, w.blk_page, w.n_tenants,
+                               w.n_pages + 8192, device="cuda:0", reserve_blocks=2048)
+    g = np.random.default_rng(3000 + seed)
+    free_pages = list(range(w.n_pages, w.n_pages + 8192))[::-1]
+    earlier = [w.req_tokens[w.req_off[r]: w.req_off[r + 1]] for r in range(w.n_req)]
+    inserted = evicted = 0
+
+    def lookups_agree(tag):
+        for t in range(w.n_tenants):
+            sample = [earlier[i] for i in g.choice(len(earlier), min(24, len(earlier)), replace=False)]
+            o = np.concatenate([[0], np.cumsum([len(x) for x in sample])]).astype(np.int32)
+            tk = np.concatenate(sample + [np.zeros(0, np.int32)]).astype(np.int32)
+            ten = np.full(len(sample), t, np.int32)
+            mb2 = max(max(len(x) // B for x in sample), 1)
+            ml2, pt2 = device_match(skv, dtree, o, tk, ten, mb2)
+            o_ml2, o_pt2 = otree.match(o, tk, ten, mb2)
+            assert np.array_equal(ml2, o_ml2) and np.array_equal(pt2, o_pt2), (seed, tag, t)
+
+    for rnd in range(n_rounds):
+        otree.set_epoch(rnd + 1)
+        skv.skv_set_epoch(dtree, rnd + 1)
+        reqs, off, toks, tenants = make_round(g, earlier, vocab, w.n_tenants, n_req, block_vocab)
+        mb = max(max(len(x) // B for x in reqs), 1)
+        mlen, pt = device_match(skv, dtree, off, toks, tenants, mb)
+        o_mlen, o_pt, o_ids = otree.match(off, toks, tenants, mb, want_ids=True)
+        assert np.array_equal(mlen, o_mlen) and np.array_equal(pt, o_pt), (seed, rnd)
+        new_pages = np.full((n_req, mb + 1), -1, np.int32)
+        for r, x in enumerate(reqs):
+            for j in range(len(x) // B - mlen[r] // B):
+                new_pages[r, j] = free_pages.pop()
+        first, n = skv.skv_tree_insert(dtree, off, toks, tenants, mlen, new_pages, private_copies=True)
+        o_first, o_n = otree.insert(off, toks, tenants, mlen, new_pages, private_copies=True)
+        assert np.array_equal(first, o_first) and np.array_equal(n, o_n), (seed, rnd)
+        inserted += int(n.sum())
+        # the verifier clears a random third of what is cached: public copies appear next to private ones
+        priv = otree.block_state()[0]
+        alive = np.flatnonzero(priv != 255)
+        pick = alive[g.random(len(alive)) < 0.3].astype(np.int32)
+        if len(pick):
+            skv.skv_promote(dtree, _dev(pick))
+            otree.promote(pick)
+        earlier += reqs
+        lookups_agree(rnd)
+        if rnd % 2 == 1:
+            protect = o_ids[o_ids >= 0][::3].astype(np.int32)
+            n_want = int(g.integers(0, otree.n_blocks // 4 + 1))
+            ids, pages = skv.skv_evict(dtree, n_want, protect)
+            want_ids, want_pages = otree.evict(n_want, protect)
+            assert np.array_equal(ids, want_ids) and np.array_equal(pages, want_pages), (seed, rnd)
+            evicted += len(ids)
+            free_pages += [int(p) for p in pages]
+            lookups_agree((rnd, "evicted"))
+        compare_state(skv, dtree, otree, (seed, rnd))
+        assert np.array_equal(device_epochs(skv, dtree), otree.epochs()), (seed, rnd)
+    return inserted, evicted
+
+
+def test_private_copy_streams():
+    tot = np.zeros(2, np.int64)
+    for seed in range(30):
+        print(f"[copies] stream {seed}", flush=True)
+        tot += np.array(run_copy_stream(seed))
+    assert tot[0] > 1000 and tot[1] > 200
+
+
+def test_private_copy_lookup_backtracks():
+    # the hand-made case of the oracle's pins, through the C ABI: tenant 1's own copy of X leads further than the
+    # older, public copy of X
+    skv = _skv()
+    blocks = lambda *ids: np.concatenate([np.full(B, i, np.int32) for i in ids])
+    X, Y, Z = 1, 2, 3
+    seq = blocks(X, Y)
+    args = (seq, np.array([0, 2 * B]), np.ones(2, np.uint8), np.zeros(2, np.int32), np.array([10, 11], np.int32))
+    otree = oracle.OracleTree(*args)
+    dtree = skv.skv_tree_build(*args, 3, 64, device="cuda:0", reserve_blocks=64)
+    req, off, t1 = blocks(X, Z), np.array([0, 2 * B], np.int32), np.array([1], np.int32)
+    mlen, _ = device_match(skv, dtree, off, req, t1, 2)
+    assert mlen[0] == 0
+    first, n = skv.skv_tree_insert(dtree, off, req, t1, mlen, np.array([[20, 21]], np.int32), private_copies=True)
+    otree.insert(off, req, t1, mlen, np.array([[20, 21]], np.int32), private_copies=True)
+    assert (first[0], n[0]) == (0, 2)
+    skv.skv_promote(dtree, _dev(np.array([0], np.int32)))
+    otree.promote([0])
+    for q, ten in ((req, 1), (blocks(X, Y), 1), (req, 2), (blocks(X, Y), 0)):
+        ml, pt = device_match(skv, dtree, off, q, np.array([ten], np.int32), 2)
+        o_ml, o_pt = otree.match(off, q, np.array([ten], np.int32), 2)
+        assert np.array_equal(ml, o_ml) and np.array_equal(pt, o_pt), (ten,)
+    ml, pt = device_match(skv, dtree, off, req, t1, 2)
+    otree.match(off, req, t1, 2)
+    assert ml[0] == 2 * B and list(pt[0]) == [20, 21]
+    compare_state(skv, dtree, otree, "backtrack")
+
+
+def test_private_copies_config3_full_size():
+    """Full size: every request of config 3 adds its own copy of what it could not see; asked again, each request
+    now reuses its whole prompt; other tenants gain nothing from the private copies; all of it agrees with the
+    oracle, counters included."""
+    skv = _skv()
+    w = inputs.config3()
+    otree = oracle.OracleTree.from_workload(w)
+    nb_req = int((np.diff(w.req_off) // B).sum())
+    dtree = skv.skv_tree_build(w.seq_tokens, w.seq_off, w.blk_sensitive, w.blk_owner, w.blk_page, w.n_tenants,
+                               w.n_pages + nb_req, device="cuda:0", reserve_blocks=nb_req)
+    mb = max(w.max_blocks, 1)
+    mlen, pt = device_match(skv, dtree, w.req_off, w.req_tokens, w.req_tenant, mb)
+    o_mlen, _ = otree.match(w.req_off, w.req_tokens, w.req_tenant, mb)
+    assert np.array_equal(mlen, o_mlen)
+    full = np.diff(w.req_off) // B - mlen // B
+    new_pages = np.full((w.n_req, int(full.max())), -1, np.int32)
+    new_pages[np.arange(new_pages.shape[1])[None, :] < full[:, None]] = w.n_pages + np.arange(int(full.sum()), dtype=np.int32)
+    first, n = skv.skv_tree_insert(dtree, w.req_off, w.req_tokens, w.req_tenant, mlen, new_pages, private_copies=True)
+    o_first, o_n = otree.insert(w.req_off, w.req_tokens, w.req_tenant, mlen, new_pages, private_copies=True)
+    assert np.array_equal(first, o_first) and np.array_equal(n, o_n)
+    print(f"[copies] c3: {int(n.sum())} of {int(full.sum())} suffix blocks inserted", flush=True)
+    for shift in (0, 1):
+        ten = ((w.req_tenant + shift) % w.n_tenants).astype(np.int32)
+        ml2, pt2 = device_match(skv, dtree, w.req_off, w.req_tokens, ten, mb)
+        o_ml2, o_pt2 = otree.match(w.req_off, w.req_tokens, ten, mb)
+        assert np.array_equal(ml2, o_ml2) and np.array_equal(pt2, o_pt2)
+        if shift == 0:
+            assert np.array_equal(ml2 // B, np.diff(w.req_off) // B)      # the stream now feeds itself completely
+            print(f"   reuse before {int(mlen.sum())} tokens, after {int(ml2.sum())}", flush=True)
+    compare_state(skv, dtree, otree, "c3 copies")
