@@ -116,3 +116,37 @@ def test_window_roll_argument_checks(skv):
     ok = skv.rdr_policy()
     assert l.skv_window_roll(None, C.byref(ok), None, None) == -1
     assert l.skv_block_state_read(None, None, None, None, None) == -1
+
+
+def test_insert_evict_scatter_decode_argument_checks(skv):
+    l = skv.lib()
+    n = C.c_size_t()
+    k = C.c_int64()
+    # tree-side calls need a tree handle
+    assert l.skv_tree_insert(None, 1, None, None, None, None, None, 0, 0, None, None, None) == -1
+    assert l.skv_evict(None, 1, None, 0, None, None, C.byref(k), None) == -1
+    assert l.skv_promote(None, None, 0, None) == -1
+    assert l.skv_set_epoch(None, 3) == -1
+    assert l.skv_block_epochs_read(None, None, None) == -1
+    assert l.skv_tree_size_for_capacity(-1, C.byref(n)) == -1
+    assert l.skv_tree_size_for_capacity(1 << 40, C.byref(n)) == -3
+    assert l.skv_tree_size_for_capacity(1000, C.byref(n)) == 0 and n.value % 256 == 0 and n.value >= 1000 * 200
+    small, big = C.c_size_t(), C.c_size_t()
+    l.skv_tree_size_for_capacity(10, C.byref(small))
+    l.skv_tree_size_for_capacity(11, C.byref(big))
+    assert big.value >= small.value
+    # scatter: description and pointers
+    good = skv.attn_desc(32, 8, 128, "bf16")
+    assert l.skv_scatter_kv(None, 1, None, None, None, None, 1, None, None, 4, None) == -1
+    assert l.skv_scatter_kv(C.byref(good), 1, None, None, None, None, 1, None, None, 4, None) == -1   # null tensors
+    assert l.skv_scatter_kv(C.byref(good), 0, None, None, None, None, 1, None, None, 4, None) == 0    # empty batch
+    assert l.skv_scatter_kv(C.byref(skv.AttnDesc(8, 2, 128, 9, 1.0)), 1, None, None, None, None, 1, None, None, 4, None) == -1
+    # decode: bf16, d 128, at most 16 query heads per kv head
+    for bad in (skv.attn_desc(8, 2, 64, "bf16"), skv.attn_desc(8, 2, 128, "f32"), skv.attn_desc(34, 2, 128, "bf16"),
+                skv.attn_desc(8, 3, 128, "bf16")):
+        assert l.skv_decode_attn_workspace_size(C.byref(bad), 4, 16, C.byref(n)) == -1
+    assert l.skv_decode_attn_workspace_size(C.byref(good), 4, 16, C.byref(n)) == 0 and n.value > 0
+    assert l.skv_decode_attn_workspace_size(C.byref(good), -1, 16, C.byref(n)) == -1
+    args = [None, None, None, 4, None, None, 16, None, None, 0, None]
+    assert l.skv_decode_attn(C.byref(good), 4, *args) == -1          # null tensors
+    assert l.skv_decode_attn(C.byref(good), 0, *args) == 0           # empty batch
