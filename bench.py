@@ -176,6 +176,16 @@ def main():
     t_roll = sg[0].elapsed_time(sg[1]) * 1e-3 / 10
     n_tree_blocks = sess.tree.info()["n_blocks"]
 
+    # the lookup call alone (skv_match: walk + counter atomics), back to back; the step's "match" stage above also
+    # holds the counter reset and the suffix-offset scan
+    sg[0].record()
+    for _ in range(50):
+        skv.skv_match(sess.tree, sess.req_off, sess.req_tokens, sess.req_tenant, sess.max_blocks, sess.matched_len,
+                      sess.page_table)
+    sg[1].record()
+    torch.cuda.synchronize()
+    t_match_only = sg[0].elapsed_time(sg[1]) * 1e-3 / 50
+
     # insert side, outside the timed region: the suffixes' full blocks written to fresh pages (read + write, K and V)
     q_off_h = sess.q_off.cpu().numpy()
     full = np.diff(q_off_h) // 16
@@ -247,6 +257,7 @@ def main():
                    "requests": w.n_req, "prompt_tokens": int(tokens), "reused_tokens": int(mlen.sum()),
                    "reuse_rate": float(mlen.sum()) / tokens},
         "lookups_per_s": w.n_req / t_match,
+        "lookups_per_s_match_call_only": w.n_req / t_match_only,
         "computed_tokens_per_s": (tokens - float(mlen.sum())) / t_attn,
         "stage_ms": {"match": t_match * 1e3, "gather": t_gather * 1e3, "attention": t_attn * 1e3},
         "gather_gbs": gather_bytes / t_gather / 1e9 if mlen.sum() else 0.0,

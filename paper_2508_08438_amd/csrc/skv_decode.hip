@@ -131,8 +131,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attn_kernel(DecParams p) {
       const int nrec = n_valid * (int)row_bytes;
       const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(lane_bcast(ak_w, idx), 0, nrec, 0x00020000);
       const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(lane_bcast(av_w, idx), 0, nrec, 0x00020000);
-      kreg[cc] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rk, (int)t_off, 0, 0));
-      vreg[cc] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rv, (int)t_off, 0, 0));
+      // cache policy 2 = non-temporal: every byte is used once, so the stream should not displace what L2 holds
+      kreg[cc] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rk, (int)t_off, 0, 2));
+      vreg[cc] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rv, (int)t_off, 0, 2));
     }
   };
   const int k_lds = t_row * kKsStride + (tid & 15) * 8;
