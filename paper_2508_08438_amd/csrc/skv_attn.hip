@@ -139,9 +139,13 @@ struct Softmax {
 };
 
 __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
-  __shared__ __attribute__((aligned(16))) __bf16 smem[kKStages * kBN * kKsStride + kVStages * kBN * kVsStride];
+  __shared__ __attribute__((aligned(16))) __bf16 smem[kKStages * kBN * kKsStride + kVStages * kBN * kVsStride +
+                                                      kWaves * kRowsPerWave * kD];
   __bf16* const Ks = smem;                                // [kKStages][kBN][kKsStride]
   __bf16* const Vs = smem + kKStages * kBN * kKsStride;    // [kVStages][kBN][kVsStride]
+  // [kWaves][32 rows][16 chunks of 8 bf16]: each wave's own staging tile for its Q rows on the way in and its O rows
+  // on the way out, 16-byte chunks XOR-swizzled by row so that row-wise and fragment-wise accesses are conflict free
+  __bf16* const stage = Vs + kVStages * kBN * kVsStride + (threadIdx.x >> 6) * (kRowsPerWave * kD);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -188,12 +192,24 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   const int wave_key_end = pos0 < S ? L + min(S, pos0 + kRowsPerWave) : 0;    // this wave needs keys [0, wave_key_end)
 
   // ---- Q fragments (B operand of S^T = K Q^T): lane holds query l32, d = 16 ks + 8 half .. +7
+  // Rows are fetched whole (16 lanes x 16 B per row) into the wave's staging tile and picked up from there.
   bf16x8 qf[8];
   {
-    const int row = max(min(pos0 + l32, S - 1), 0);
-    const __bf16* src = (const __bf16*)p.q + ((size_t)(qbase + row) * p.Hq + head) * kD + 8 * half;
+    const int c16 = lane & 15;
+    u32x4 qv[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8*)(src + ks * 16);
+    for (int i = 0; i < 8; ++i) {
+      const int rr = (lane >> 4) + 4 * i;
+      const int row = max(min(pos0 + rr, S - 1), 0);
+      qv[i] = *(const u32x4*)((const __bf16*)p.q + ((size_t)(qbase + row) * p.Hq + head) * kD + c16 * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int rr = (lane >> 4) + 4 * i;
+      *(u32x4*)(stage + rr * kD + ((c16 ^ (rr & 15)) << 3)) = qv[i];
+    }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8*)(stage + l32 * kD + (((2 * ks + half) ^ (l32 & 15)) << 3));
   }
 
   f32x16 o[4];   // O^T accumulators: d = 32 a + 8(e/4) + 4 half + e%4, query = l32
@@ -388,14 +404,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
     __syncthreads();
   }
 
-  // ---- normalise and store: lane holds query l32; d = 32 a + 8 (e/4) + 4 half + e%4
+  // ---- normalise and store.  A lane holds query l32 with d = 32 a + 8 (e/4) + 4 half + e%4, i.e. sixteen 8-byte
+  // pieces of one output row.  They go through the wave's staging tile and leave as whole 256-byte rows.
   if (pos0 >= S) return;
   {
     const float lsum = sm.l_run + swap_halves(sm.l_run);
     const float inv = 1.0f / lsum;
-    const int pos = pos0 + l32;
-    if (pos < S) {
-      __bf16* dst = (__bf16*)p.out + ((size_t)(qbase + pos) * p.Hq + head) * kD + 4 * half;
+    {
+      __bf16* row = stage + l32 * kD;
 #pragma unroll
       for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -405,8 +421,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
           bf16x2 y0 = __builtin_convertvector(x0, bf16x2);
           bf16x2 y1 = __builtin_convertvector(x1, bf16x2);
           u32x2 wv = {__builtin_bit_cast(uint32_t, y0), __builtin_bit_cast(uint32_t, y1)};
-          *(u32x2*)(dst + a * 32 + i4 * 8) = wv;
+          const int chunk = a * 4 + i4;   // d = 8 chunk + 4 half .. + 3
+          *(u32x2*)(row + (((chunk ^ (l32 & 15)) << 3) + 4 * half)) = wv;
         }
+    }
+    // same wave wrote and reads: the LDS operations of one wave complete in order
+    const int c16 = lane & 15;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int rr = (lane >> 4) + 4 * i;   // row of this wave's tile
+      const int pos = pos0 + rr;
+      const u32x4 v = *(const u32x4*)(stage + rr * kD + ((c16 ^ (rr & 15)) << 3));
+      if (pos < S) *(u32x4*)((__bf16*)p.out + ((size_t)(qbase + pos) * p.Hq + head) * kD + c16 * 8) = v;
     }
   }
 }
