@@ -120,6 +120,10 @@ def main():
     ap.add_argument("--calib-mib", type=int, default=0,
                     help="also run one plain streaming kernel (out = 2 * in over this many MiB of fp32) outside the "
                          "timed region, as the known-size reference for HBM traffic counters")
+    ap.add_argument("--p-sensitive", type=float, default=None,
+                    help="config 5 only: fraction of cached blocks marked sensitive (0, 0.25, 0.5 or 1; nested sets)")
+    ap.add_argument("--cold", action="store_true",
+                    help="also time each stage after flushing L2 / Infinity Cache (512 MiB written between stages)")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-step attention measurement")
     ap.add_argument("--cpu-rows", type=int, default=262144, help="oracle attention rows to time (0 = skip)")
     args = ap.parse_args()
@@ -133,7 +137,11 @@ def main():
     from paper_2508_08438_amd.pipeline import Session
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    w = inputs.CONFIGS[args.workload](hard=args.hard)
+    if args.p_sensitive is not None:
+        assert args.workload == "c5", "--p-sensitive belongs to config 5"
+        w = inputs.config5(p_sensitive=args.p_sensitive, hard=args.hard)
+    else:
+        w = inputs.CONFIGS[args.workload](hard=args.hard)
     sess = Session(w, device="cuda:0")
     sess.prepare()
     mlen = sess.host_matched_len.copy()
@@ -162,9 +170,58 @@ def main():
     elapsed = time.perf_counter() - t0
     ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev])
     t_match, t_gather, t_attn = (float(x) * 1e-3 for x in ms.mean(0))
+    step_ms = ms.sum(1)
+
+    from paper_2508_08438_amd import binding as skv
+    # the counters after one step of this batch: what the safeguard would read (reuse statistics of the workload)
+    hit, ucnt = sess.counters()
+    used = hit > 0
+    rdr = ucnt[used] / hit[used]
+    reuse_stats = {"sum_hit": int(hit.sum()), "blocks_hit": int(used.sum()),
+                   "rdr_histogram_10_bins_0_to_1": np.histogram(rdr, bins=10, range=(0.0, 1.0))[0].tolist()}
+
+    stage_ms_cold = None
+    if args.cold:
+        flush = torch.zeros(512 << 18, dtype=torch.float32, device=sess.device)   # 512 MiB
+        ce = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+        acc = np.zeros(3)
+        for _ in range(5):
+            for i, stage in enumerate((sess.match, sess.gather, sess.attention)):
+                flush.add_(1.0)
+                ce[2 * i].record()
+                stage()
+                ce[2 * i + 1].record()
+            torch.cuda.synchronize()
+            acc += np.array([ce[2 * i].elapsed_time(ce[2 * i + 1]) for i in range(3)])
+        stage_ms_cold = dict(zip(("match", "gather", "attention"), (acc / 5).tolist()))
+        del flush
+
+    # a sixteen times longer request stream in one launch (the batch repeated with re-drawn tenants): steady-state
+    # lookups/s, where the single batch mostly measures launch latency
+    rep = 16
+    g16 = np.random.default_rng(16)
+    lens = np.diff(w.req_off)
+    off16 = np.concatenate([[0], np.cumsum(np.tile(lens, rep))]).astype(np.int64)
+    x16 = None
+    if off16[-1] < 2 ** 31 and w.n_req * rep * sess.max_blocks < 2 ** 30:
+        ten16 = g16.integers(0, w.n_tenants, w.n_req * rep).astype(np.int32)
+        d_off16 = torch.from_numpy(off16.astype(np.int32)).to(sess.device)
+        d_tok16 = sess.req_tokens.repeat(rep)
+        d_ten16 = torch.from_numpy(ten16).to(sess.device)
+        d_len16 = torch.zeros(w.n_req * rep, dtype=torch.int32, device=sess.device)
+        d_pt16 = torch.empty((w.n_req * rep, sess.max_blocks), dtype=torch.int32, device=sess.device)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        skv.skv_match(sess.tree, d_off16, d_tok16, d_ten16, sess.max_blocks, d_len16, d_pt16)
+        e0.record()
+        for _ in range(10):
+            skv.skv_match(sess.tree, d_off16, d_tok16, d_ten16, sess.max_blocks, d_len16, d_pt16)
+        e1.record()
+        torch.cuda.synchronize()
+        x16 = {"requests": w.n_req * rep, "ms": e0.elapsed_time(e1) / 10,
+               "lookups_per_s": w.n_req * rep / (e0.elapsed_time(e1) * 1e-3 / 10)}
+        del d_pt16, d_tok16
 
     # safeguard step (window roll + RDR scan), outside the timed region: a streaming pass over the block records
-    from paper_2508_08438_amd import binding as skv
     pol = skv.rdr_policy(direction=0, tau=(1, 2), min_hits=2, n_consec=2)
     sg = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     skv.skv_window_roll(sess.tree, pol)
@@ -249,7 +306,8 @@ def main():
     out = {
         "metric": "selective-reuse prefill tokens/s + prefix-match lookups/s on 1 MI355X",
         "value": tokens * K / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
-        "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": elapsed / K * 1e3, "ms_per_step_median": float(np.median(step_ms)),
+        "ms_per_step_min": float(step_ms.min()), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": a.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}{'_hard' if args.hard else ''}: {w.n_req} requests, {w.n_tenants} tenants, "
                                f"{int(tokens)} prompt tokens, {int(mlen.sum())} reused, "
@@ -258,6 +316,9 @@ def main():
                    "reuse_rate": float(mlen.sum()) / tokens},
         "lookups_per_s": w.n_req / t_match,
         "lookups_per_s_match_call_only": w.n_req / t_match_only,
+        "lookups_x16_stream": x16,
+        "reuse_stats": reuse_stats,
+        "stage_ms_cold_cache": stage_ms_cold,
         "computed_tokens_per_s": (tokens - float(mlen.sum())) / t_attn,
         "stage_ms": {"match": t_match * 1e3, "gather": t_gather * 1e3, "attention": t_attn * 1e3},
         "gather_gbs": gather_bytes / t_gather / 1e9 if mlen.sum() else 0.0,
