@@ -30,9 +30,19 @@
 //    and which direction is "right" is parity unpinned.  The mechanics for a given parameter set are
 //    pinned against an independent recomputation from the counters.
 //
-// Pins: brute-force prefix scans, the 0 % / 100 % sensitive special cases, the visibility
-// invariants, counter conservation, and closed-form / library attention cases, all in the
-// CPU test-suite.  Unpinned: nothing in this file (the RDR *decision* is not implemented here).
+//  * Insert after prefill (Section 4.3.1 Insert, Section 4.2.1: new blocks start private), promotion as a flag
+//    flip (Section 4.2.3), per-tenant copies of the same content with a depth-first longest-visible-path search
+//    (Section 4.1), access epochs and block-by-block eviction of the oldest unprotected childless tail
+//    (Section 4.3.1 Evict, Section 4.3.2 progressive eviction), and the byte copy of new KV blocks into pool
+//    pages.
+//
+// Pins (all in the CPU test-suite): brute-force prefix scans, the 0 % / 100 % sensitive special cases, the
+// visibility invariants, counter conservation, closed-form / library attention cases; the safeguard step against
+// an independent recomputation with exact fractions; insert, eviction and copies against models without any tree
+// (a dictionary of whole block-prefixes, a flat entry list with parent links).
+// Parity unpinned: WHICH safeguard policy (trigger direction, threshold) and WHICH eviction policy (tie-break,
+// what counts as "in use") the paper means -- it prints no example of either; what is pinned is that the readings
+// stated above are carried out exactly.
 
 #include <array>
 #include <cmath>
