@@ -163,7 +163,11 @@ void skv_tree_destroy(skv_tree* tree);
  * Writes d_matched_len[r] = 16*k_r and d_page_table[r*max_blocks + j] = page id of block j for
  * j < k_r, -1 for k_r <= j < max_blocks.  For every matched block adds 1 to its hit counter
  * and records the tenant in its distinct-tenant set (commutative atomics: the batch result
- * does not depend on execution order).
+ * does not depend on execution order), and stamps the block with the current epoch (skv_set_epoch).
+ * On a tree that holds per-tenant copies (skv_tree_insert with private_copies) a position can offer several
+ * children that start with the request's next block; the walk then follows every copy whose first block the
+ * tenant may see and the longest path wins, as described at skv_tree_insert; only that path's blocks are
+ * counted and stamped.
  * A request whose tenant is outside [0, n_tenants) or whose offsets decrease matches nothing.
  * Errors: SKV_EINVAL for null pointers or negative sizes.  n_req == 0 is a no-op. */
 int skv_match(skv_tree* tree, int32_t n_req, const int32_t* d_req_off, const int32_t* d_req_tokens,
