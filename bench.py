@@ -128,7 +128,7 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=262144, help="oracle attention rows to time (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build measures the path on ONE GPU; --gpus N with N > 1 is not supported "
+        sys.exit("bench.py: the path is measured on ONE GPU; --gpus N with N > 1 is not supported "
                  "(no collectives or sharding are part of it)")
 
     import numpy as np
