@@ -8,13 +8,14 @@
 //
 // bf16 path: flash-style streaming over 64-key tiles with online softmax in fp32; the two
 // contractions (K.Q^T and V^T.P^T) run on the matrix cores (v_mfma_f32_32x32x16_bf16), the
-// softmax on the vector ALU.  A workgroup of four wavefronts shares every K/V tile through
-// LDS; each wavefront owns 64 query rows of one head (the query heads of one kv head share a
-// workgroup, so a K/V tile is fetched once for the group).  The products are formed
-// transposed (S^T = K Q^T, O^T = V^T P^T) so that a query is a lane-column of the MFMA
+// softmax on the vector ALU.  A workgroup of eight wavefronts shares every K/V tile through
+// LDS; each wavefront owns 32 query rows of one head (the query heads of one kv head share a
+// workgroup, so a K/V tile is fetched once for the group).  K/V rows travel global -> LDS with
+// direct-to-LDS loads (no stop in registers, no LDS store instructions).  The products are
+// formed transposed (S^T = K Q^T, O^T = V^T P^T) so that a query is a lane-column of the MFMA
 // accumulator: row max / row sum are register reductions plus one cross-half exchange, and
-// the P^T accumulator registers are already in the B-operand layout of the second product
-// once V^T is stored in LDS with the matching key permutation.
+// the P^T accumulator registers are already in the B-operand layout of the second product;
+// V^T fragments come from the LDS transpose load.
 // fp32 path: one wavefront per output row, plain fp32 arithmetic (correctness configuration).
 #include "skv_internal.h"
 
@@ -38,8 +39,15 @@ constexpr float kRescaleLog2 = 8.f;  // move the softmax reference when a row ma
 constexpr int kRowsPerWave = 32; // query rows per wavefront
 constexpr int kWaves = 8;        // two per SIMD: one wave's softmax overlaps the other's MFMAs
 constexpr int kThreads = kWaves * 64;
-constexpr int kKsStride = kD + 8;    // bf16 elements per K row in LDS (272 B: conflict-free b128 reads)
-constexpr int kVsStride = kD + 32;    // bf16 elements per V row in LDS (320 B: conflict-free transpose loads)
+// LDS tile layout (K and V alike): a 64-key tile is 16 segments of 4 keys, 1040 bytes apart.  Inside a segment the
+// 16-byte piece (key q of the segment, chunk c of the 256-byte row) sits at (c / 4) * 256 + q * 64 + (c % 4) * 16.
+// One direct-to-LDS load of a wavefront fills one segment: the hardware puts what lane i fetched at byte 16 i, so
+// lane i fetches chunk 4 (i / 16) + i % 4 of key (i / 4) % 4 -- four lanes read 64 consecutive bytes of a row.
+// The K fragment reads (ds_read_b128: 16 lanes = 16 keys, one chunk) and the V^T fragment reads
+// (ds_read_b64_tr_b16: 32 lanes = 4 keys x 64 bytes) are free of bank conflicts, and the addresses of different
+// fragments differ by constants only.
+constexpr int kSeg = 520;            // bf16 elements per segment (1040 B)
+constexpr int kTile = 16 * kSeg;     // bf16 elements per 64-key tile
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct AttnParams {
@@ -48,6 +56,7 @@ struct AttnParams {
   const int32_t *q_off, *matched_len, *page_table;
   const int32_t* items;      // kItemInts ints per work item
   const int32_t* n_items;
+  const char* zero_page;     // 16 rows of zeros: stands in for a group of keys that has no data
   int n_req, max_blocks, n_pages, Hq, Hkv;
   int heads_per_wg;          // query heads of one kv head handled by one workgroup (1, 2 or 4)
   float scale;
@@ -60,8 +69,10 @@ struct AttnParams {
 constexpr int kItemInts = 8;
 __global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_off,
                                      const int32_t* __restrict__ matched_len, int pos_per_wg,
-                                     int max_items, int32_t* __restrict__ n_items, int32_t* __restrict__ items) {
+                                     int max_items, int32_t* __restrict__ n_items, int32_t* __restrict__ items,
+                                     uint4* __restrict__ zero_page, int zero_vec) {
   __shared__ int32_t sh[1024];
+  for (int i = threadIdx.x; i < zero_vec; i += 1024) zero_page[i] = make_uint4(0u, 0u, 0u, 0u);
   __shared__ int32_t carry;
   if (threadIdx.x == 0) carry = 0;
   __syncthreads();
@@ -98,32 +109,6 @@ __global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_of
 }
 
 // ---- bf16 MFMA kernel --------------------------------------------------------------------------
-struct RowSrc {          // where one 16-key group of a tile lives
-  const __bf16* k;       // first row of the group for this kv head (always a readable address)
-  const __bf16* v;
-  int n_valid;           // rows of the group that exist (0..16); rows beyond are read as zeros
-};
-
-// All arguments are wave-uniform, so this is scalar code.  `page` is the page-table entry of the
-// group when it lies in the reused prefix.  A group without data (past the end, or a page id outside
-// the pool) points at the request's first new row, which always exists, and reports no valid rows.
-__device__ inline RowSrc group_source(const AttnParams& p, int kvh, int L, int Ltot, int qbase, int key0, int page) {
-  RowSrc s;
-  if (key0 < L && page >= 0 && page < p.n_pages) {
-    const size_t off = ((size_t)page * SKV_BLOCK_TOKENS * p.Hkv + kvh) * kD;
-    s.k = (const __bf16*)p.kpool + off;
-    s.v = (const __bf16*)p.vpool + off;
-    s.n_valid = 16;
-  } else {
-    const bool is_new = key0 >= L && key0 < Ltot;
-    const size_t off = ((size_t)(qbase + (is_new ? key0 - L : 0)) * p.Hkv + kvh) * kD;
-    s.k = (const __bf16*)p.knew + off;
-    s.v = (const __bf16*)p.vnew + off;
-    s.n_valid = is_new ? min(16, Ltot - key0) : 0;
-  }
-  return s;
-}
-
 // Value of the lane 32 positions away (the other half of the wavefront): v_permlane32_swap exchanges the
 // upper half of its first operand with the lower half of its second.
 __device__ inline float swap_halves(float x) {
@@ -139,13 +124,13 @@ struct Softmax {
 };
 
 __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
-  __shared__ __attribute__((aligned(16))) __bf16 smem[kKStages * kBN * kKsStride + kVStages * kBN * kVsStride +
+  __shared__ __attribute__((aligned(16))) __bf16 smem[kKStages * kTile + kVStages * kTile +
                                                       kWaves * kRowsPerWave * kD];
-  __bf16* const Ks = smem;                                // [kKStages][kBN][kKsStride]
-  __bf16* const Vs = smem + kKStages * kBN * kKsStride;    // [kVStages][kBN][kVsStride]
+  __bf16* const Ks = smem;
+  __bf16* const Vs = smem + kKStages * kTile;
   // [kWaves][32 rows][16 chunks of 8 bf16]: each wave's own staging tile for its Q rows on the way in and its O rows
   // on the way out, 16-byte chunks XOR-swizzled by row so that row-wise and fragment-wise accesses are conflict free
-  __bf16* const stage = Vs + kVStages * kBN * kVsStride + (threadIdx.x >> 6) * (kRowsPerWave * kD);
+  __bf16* const stage = Vs + kVStages * kTile + (threadIdx.x >> 6) * (kRowsPerWave * kD);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -221,59 +206,71 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   const float c = p.scale * kLog2e;
   const float thr = kRescaleLog2 / c;  // raw-score distance above the reference that forces a rescale
 
-  // ---- global -> register staging -> LDS ----
-  // A tile is four 16-key groups; a group is one page of the pool or 16 consecutive new rows, so
-  // its base address is wave-uniform (scalar) and each thread adds a fixed offset.  K and V rows go
-  // to LDS as they are (row = key); the PV product reads V through the LDS transpose load.
-  u32x4 kreg[2], vreg[2];
+  // ---- global -> LDS, without a stop in registers ----
+  // A tile is four 16-key groups; a group is one page of the pool or 16 consecutive new rows.  Each wavefront
+  // moves two K and two V segments of a tile (segments w and w + 8: keys 4w.. and 32 + 4w..) with direct-to-LDS
+  // loads: lane i fetches chunk 4 (i / 16) + i % 4 of key (i / 4) % 4 of the segment and the hardware puts it at slot i.
   const unsigned row_bytes = (unsigned)p.Hkv * kD * 2u;
-  const int t_row = (tid >> 4) & 15;                         // 16 threads x 16 B per key row
-  const unsigned t_off = (unsigned)t_row * row_bytes + (unsigned)(tid & 15) * 16u;
-  const int t_grp = wave >> 2;                               // + 2 cc: the 16-key group of chunk cc
-
-  // Page ids of the next 64 key groups (16 tiles) sit one per lane in a register; the group's id is
-  // read with a lane broadcast, so no memory latency sits between tiles.  Window w covers tiles
-  // 16w .. 16w+15 and is fetched one iteration before its first use.
-  const int n_prefix_groups = L / SKV_BLOCK_TOKENS;
-  auto fetch_window = [&](int w) __attribute__((always_inline)) {
+  const int t_row = (wave & 3) * 4 + ((lane >> 2) & 3);      // row of the 16-key group this lane fetches
+  const unsigned t_col = (unsigned)((lane >> 4) * 4 + (lane & 3)) * 16u;
+  const unsigned t_off = (unsigned)t_row * row_bytes + t_col;
+  // Group base addresses, one 16-key group per lane for the next 64 groups (16 tiles): a pool page, 16 new rows,
+  // or the page of zeros when the group has no data (past the end of the sequence, or a page id outside the pool).
+  // A tile's bases are read with lane broadcasts.  Window w is fetched one iteration before its first use.
+  auto fetch_window = [&](int w, uint64_t& ak, uint64_t& av) __attribute__((always_inline)) {
     const int gi = w * 64 + lane;
-    int v = -1;
-    if (gi < n_prefix_groups && gi < p.max_blocks) v = p.page_table[(size_t)r * p.max_blocks + gi];
-    return v;
+    const int key0 = gi * SKV_BLOCK_TOKENS;
+    uint64_t k = (uint64_t)p.zero_page, v = k;
+    if (key0 < L) {
+      if (gi < p.max_blocks) {
+        const int page = p.page_table[(size_t)r * p.max_blocks + gi];
+        if (page >= 0 && page < p.n_pages) {
+          const uint64_t off = ((uint64_t)page * SKV_BLOCK_TOKENS * p.Hkv + kvh) * (kD * 2);
+          k = (uint64_t)p.kpool + off;
+          v = (uint64_t)p.vpool + off;
+        }
+      }
+    } else if (key0 < Ltot) {
+      const uint64_t off = ((uint64_t)(qbase + key0 - L) * p.Hkv + kvh) * (kD * 2);
+      k = (uint64_t)p.knew + off;
+      v = (uint64_t)p.vnew + off;
+    }
+    ak = k;
+    av = v;
   };
-  int pt_cur = fetch_window(0), pt_nxt = -1;
+  auto lane_bcast = [&](uint64_t x, int idx) __attribute__((always_inline)) {
+    const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)x, idx);
+    const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), idx);
+    return (const __attribute__((address_space(1))) char*)(((uint64_t)hi << 32) | lo);   // global, not flat
+  };
+  uint64_t ak_cur, av_cur, ak_nxt = 0, av_nxt = 0;
+  fetch_window(0, ak_cur, av_cur);
+  typedef __attribute__((address_space(3))) void lds_void;
   auto load_tile = [&](int kt) __attribute__((always_inline)) {
     const int key_base = kt * kBN;
+    __bf16* const kdst = Ks + (kt % kKStages) * kTile + wave * kSeg;
+    __bf16* const vdst = Vs + (kt % kVStages) * kTile + wave * kSeg;
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc) {
-      const int g = cc * 2 + t_grp;
-      const int page = __builtin_amdgcn_readlane(pt_cur, ((kt & 15) << 2) + g);
-      const RowSrc src = group_source(p, kvh, L, Ltot, qbase, key_base + g * 16, page);
-      if (src.n_valid == 16) {
-        kreg[cc] = *(const u32x4*)((const char*)src.k + t_off);
-        vreg[cc] = *(const u32x4*)((const char*)src.v + t_off);
-      } else {  // ragged end of the sequence or a page id outside the pool: missing rows read as zeros
-        const bool ok = t_row < src.n_valid;
-        const unsigned off = ok ? t_off : (unsigned)(tid & 15) * 16u;
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        const u32x4 kv = *(const u32x4*)((const char*)src.k + off);
-        const u32x4 vv = *(const u32x4*)((const char*)src.v + off);
-        kreg[cc] = ok ? kv : z;
-        vreg[cc] = ok ? vv : z;
+      const int g = (wave >> 2) + 2 * cc;                    // 16-key group of segment wave + 8 cc
+      const int idx = ((kt & 15) << 2) + g;
+      const auto kb = lane_bcast(ak_cur, idx);
+      const auto vb = lane_bcast(av_cur, idx);
+      unsigned off = t_off;
+      if (key_base + kBN > Ltot) {  // the sequence ends inside this tile: rows past its end re-read its last row,
+        const int n_valid = Ltot - (key_base + g * 16);  // finite values that the causal mask keeps out
+        if (n_valid > 0 && n_valid < 16) off = (unsigned)min(t_row, n_valid - 1) * row_bytes + t_col;
       }
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kb + off),
+                                       (lds_void*)(kdst + cc * 8 * kSeg), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vb + off),
+                                       (lds_void*)(vdst + cc * 8 * kSeg), 16, 0, 0);
     }
   };
-  const int k_lds = (tid >> 4) * kKsStride + (tid & 15) * 8;  // + 32 cc rows
-  const int v_lds = (tid >> 4) * kVsStride + (tid & 15) * 8;
-  auto store_k = [&](int kt) __attribute__((always_inline)) {
-    __bf16* dst = Ks + (kt % kKStages) * (kBN * kKsStride) + k_lds;
-    *(u32x4*)(dst) = kreg[0];
-    *(u32x4*)(dst + 32 * kKsStride) = kreg[1];
-  };
-  auto store_v = [&](int kt) __attribute__((always_inline)) {
-    __bf16* dst = Vs + (kt % kVStages) * (kBN * kVsStride) + v_lds;
-    *(u32x4*)(dst) = vreg[0];
-    *(u32x4*)(dst + 32 * kVsStride) = vreg[1];
+  // a wave's direct loads are in LDS once its vector-memory counter has drained; the barrier then publishes them
+  auto tile_barrier = [&]() __attribute__((always_inline)) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
   };
 
   // ---- the phases of a tile ----
@@ -283,24 +280,28 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   f32x16 s[2];   // S^T of the current tile: [64 keys][32 queries] as two 32x32 tiles
   bf16x8 pb[4];  // P^T as B operands, one per 16-key group
   bf16x8 fr[8];  // fragment ring: K fragments during QK, V^T fragments during PV
-  const int k_lane = l32 * kKsStride + 8 * half;
+  // K fragment (ks, mt): lane (l32, half) wants key l32 + 32 mt, chunk 2 ks + half.  In bf16 elements:
+  //   segment (l32 / 4 + 8 mt) * kSeg + key-in-segment (l32 % 4) * 32 + (ks / 2) * 128 + (2 (ks % 2) + half) * 8
+  const int k_lane = (l32 >> 2) * kSeg + (l32 & 3) * 32 + half * 8;
   // The PV A operand wants, per lane (d = 32 a + l32), the eight keys {4 half + 0..3, 8 + 4 half + 0..3}
   // of a 16-key group -- the keys this lane-half's P^T registers hold.  Each quad comes from one LDS
   // transpose load: within 16 lanes, lane i supplies the address of 4 consecutive d of key (i / 4) at d
-  // offset 4 (i % 4) and receives d offset i of the four keys.
-  const int v_lane = (4 * half + ((lane & 15) >> 2)) * kVsStride + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  // offset 4 (i % 4) and receives d offset i of the four keys.  For fragment (g16, a) the lane's key is
+  // 16 g16 + 4 half + (lane % 16) / 4 (segment 4 g16 + half, second load two segments on) and its 8 bytes are piece
+  // lane % 2 of chunk 4 a + 2 ((lane / 16) % 2) + (lane % 4) / 2.
+  const int v_lane = half * kSeg + ((lane & 15) >> 2) * 32 + (2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) * 8 + 4 * (lane & 1);
   auto k_frag = [&](const __bf16* kb, int j) __attribute__((always_inline)) {   // fragment j = (ks, mt) = (j / 2, j % 2)
-    return *(const bf16x8*)(kb + (j & 1) * 32 * kKsStride + (j >> 1) * 16);
+    return *(const bf16x8*)(kb + (j & 1) * 8 * kSeg + (j >> 2) * 128 + ((j >> 1) & 1) * 16);
   };
   auto v_frag = [&](const __bf16* vb, int j) __attribute__((always_inline)) {   // fragment j = (g16, a) = (j / 4, j % 4)
-    const __bf16* src = vb + (j >> 2) * 16 * kVsStride + (j & 3) * 32;
+    const __bf16* src = vb + (j >> 2) * 4 * kSeg + (j & 3) * 128;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + 8 * kVsStride));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + 2 * kSeg));
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
   // S^T = K Q^T, then the causal mask on tiles that reach past the first row's limit
   auto qk = [&](int kt) __attribute__((always_inline)) {
-    const __bf16* kb = Ks + (kt % kKStages) * (kBN * kKsStride) + k_lane;
+    const __bf16* kb = Ks + (kt % kKStages) * kTile + k_lane;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 8; ++j) fr[j] = k_frag(kb, j);
@@ -368,13 +369,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   };
   // O^T += V^T P^T : [128 d][32 queries]
   auto pv_prefetch = [&](int kt) __attribute__((always_inline)) {
-    const __bf16* vb = Vs + (kt % kVStages) * (kBN * kVsStride) + v_lane;
+    const __bf16* vb = Vs + (kt % kVStages) * kTile + v_lane;
 #pragma unroll
     for (int j = 0; j < 8; ++j) fr[j] = v_frag(vb, j);
     __builtin_amdgcn_sched_barrier(0);
   };
   auto pv = [&](int kt) __attribute__((always_inline)) {
-    const __bf16* vb = Vs + (kt % kVStages) * (kBN * kVsStride) + v_lane;
+    const __bf16* vb = Vs + (kt % kVStages) * kTile + v_lane;
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       const int g16 = j >> 2, a = j & 3;
@@ -384,24 +385,21 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
     }
   };
 
-  // ---- main loop: loads of tile kt+1 are in flight during the math on tile kt; one barrier per tile
+  // ---- main loop: the direct loads of tile kt+1 are in flight during the math on tile kt; one barrier per tile
   load_tile(0);
-  store_k(0);
-  store_v(0);
-  __syncthreads();
+  tile_barrier();
   for (int kt = 0; kt < n_tiles; ++kt) {
-    if (((kt + 1) & 15) == 0) pt_cur = pt_nxt;
+    if (((kt + 1) & 15) == 0) { ak_cur = ak_nxt; av_cur = av_nxt; }
+    // the other stage was last read one iteration ago, before the barrier every wave has passed
     if (kt + 1 < n_tiles) load_tile(kt + 1);
-    if (((kt + 2) & 15) == 0) pt_nxt = fetch_window((kt + 2) >> 4);
+    if (((kt + 2) & 15) == 0) fetch_window((kt + 2) >> 4, ak_nxt, av_nxt);
     if (kt * kBN < wave_key_end) {
       qk(kt);
       pv_prefetch(kt);
       softmax();
       pv(kt);
     }
-    // the other stage was last read one iteration ago, before the barrier every wave has passed
-    if (kt + 1 < n_tiles) { store_k(kt + 1); store_v(kt + 1); }
-    __syncthreads();
+    tile_barrier();
   }
 
   // ---- normalise and store.  A lane holds query l32 with d = 32 a + 8 (e/4) + 4 half + e%4, i.e. sixteen 8-byte
@@ -537,6 +535,10 @@ int64_t max_items_for(const skv_attn_desc* d, int32_t n_req, int64_t total_q_row
   return total_q_rows / pos_per_wg + n_req;
 }
 
+size_t zero_page_bytes(const skv_attn_desc* d) {
+  return d->dtype == SKV_BF16 ? skv_align256((size_t)SKV_BLOCK_TOKENS * d->n_kv_heads * kD * 2) : 0;
+}
+
 }  // namespace
 
 extern "C" int skv_prefill_attn_workspace_size(const skv_attn_desc* desc, int32_t n_req,
@@ -544,7 +546,7 @@ extern "C" int skv_prefill_attn_workspace_size(const skv_attn_desc* desc, int32_
   int rc = check_attn(desc);
   if (rc) return rc;
   if (n_req < 0 || total_q_rows < 0 || !bytes) return SKV_EINVAL;
-  *bytes = 256 + skv_align256((size_t)max_items_for(desc, n_req, total_q_rows) * kItemInts * sizeof(int32_t));
+  *bytes = 256 + zero_page_bytes(desc) + skv_align256((size_t)max_items_for(desc, n_req, total_q_rows) * kItemInts * sizeof(int32_t));
   return SKV_OK;
 }
 
@@ -573,7 +575,8 @@ extern "C" int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const 
   p.q = d_q; p.knew = d_knew; p.vnew = d_vnew; p.kpool = d_kpool; p.vpool = d_vpool; p.out = d_out;
   p.q_off = d_q_off; p.matched_len = d_matched_len; p.page_table = d_page_table;
   p.n_items = (const int32_t*)d_workspace;
-  p.items = (const int32_t*)((char*)d_workspace + 256);
+  p.zero_page = (const char*)d_workspace + 256;
+  p.items = (const int32_t*)((char*)d_workspace + 256 + zero_page_bytes(desc));
   p.n_req = n_req; p.max_blocks = max_blocks; p.n_pages = n_pages;
   p.Hq = desc->n_q_heads; p.Hkv = desc->n_kv_heads;
   p.heads_per_wg = heads_per_wg_for(desc->n_q_heads / desc->n_kv_heads);
@@ -596,7 +599,8 @@ extern "C" int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const 
   const int64_t grid = max_items * desc->n_kv_heads * n_hg;
   if (grid > 0x7fffffff || max_items > 0x3fffffff) return SKV_ERANGE;
   attn_schedule_kernel<<<1, 1024, 0, st>>>(n_req, d_q_off, d_matched_len, pos_per_wg, (int)max_items,
-                                           (int32_t*)d_workspace, (int32_t*)((char*)d_workspace + 256));
+                                           (int32_t*)d_workspace, (int32_t*)p.items, (uint4*)p.zero_page,
+                                           (int)(zero_page_bytes(desc) / 16));
   SKV_HIP(hipGetLastError());
   attn_bf16_kernel<<<(int)grid, kThreads, 0, st>>>(p);
   SKV_HIP(hipGetLastError());
