@@ -254,7 +254,8 @@ int skv_scatter_kv(const skv_attn_desc* desc, int32_t n_req, const void* d_knew,
                    void* d_vpool, int32_t n_pages, void* stream);
 
 /* Bytes of device workspace skv_prefill_attn needs for n_req requests and at most
- * total_q_rows uncached tokens in the batch. */
+ * total_q_rows uncached tokens in the batch (the work list of the bf16 kernel and one page of zeros that
+ * stands in for key groups without data); the call overwrites it. */
 int skv_prefill_attn_workspace_size(const skv_attn_desc* desc, int32_t n_req, int64_t total_q_rows,
                                     size_t* bytes);
 
