@@ -125,6 +125,7 @@ def main():
     ap.add_argument("--cold", action="store_true",
                     help="also time each stage after flushing L2 / Infinity Cache (512 MiB written between stages)")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-step attention measurement")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the same pass")
     ap.add_argument("--cpu-rows", type=int, default=262144, help="oracle attention rows to time (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -171,6 +172,18 @@ def main():
     ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev])
     t_match, t_gather, t_attn = (float(x) * 1e-3 for x in ms.mean(0))
     step_ms = ms.sum(1)
+
+    # the same pass recorded once as a HIP graph and replayed K times (no per-stage events, one launch per step)
+    graph_ms = None
+    if not args.no_graph:
+        sess.capture_step()
+        sess.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(K):
+            sess.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t1) / K * 1e3
 
     from paper_2508_08438_amd import binding as skv
     # the counters after one step of this batch: what the safeguard would read (reuse statistics of the workload)
@@ -314,6 +327,7 @@ def main():
                                f"GQA {a.n_q_heads}/{a.n_kv_heads} d={a.head_dim} {a.dtype}",
                    "requests": w.n_req, "prompt_tokens": int(tokens), "reused_tokens": int(mlen.sum()),
                    "reuse_rate": float(mlen.sum()) / tokens},
+        "graph_replay": None if graph_ms is None else {"ms_per_step": graph_ms, "tokens_per_s": tokens / (graph_ms * 1e-3)},
         "lookups_per_s": w.n_req / t_match,
         "lookups_per_s_match_call_only": w.n_req / t_match_only,
         "lookups_x16_stream": x16,

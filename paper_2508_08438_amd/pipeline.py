@@ -80,6 +80,24 @@ class Session:
         return {"matched_len": self.matched_len, "page_table": self.page_table, "q_off": self.q_off,
                 "ctx_off": self.ctx_off, "out": self.out, "kctx": self.kctx, "vctx": self.vctx}
 
+    # -- the same pass recorded once as a HIP graph and replayed: the calls of match / gather / attention only
+    #    enqueue kernels on the stream they are given (no allocation, no memset, no synchronisation)
+    def capture_step(self):
+        if self.q is None:
+            self.prepare()
+        self.step()                       # everything loaded and warm before the capture
+        torch.cuda.synchronize(self.device)
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self.match()
+            if self.do_gather:
+                self.gather()
+            self.attention()
+        return self.graph
+
+    def replay(self):
+        self.graph.replay()
+
     def counters(self):
         n = self.w.n_in_blocks
         hit = torch.zeros(max(n, 1), dtype=torch.int32, device=self.device)
