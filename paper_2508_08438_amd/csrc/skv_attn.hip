@@ -63,9 +63,12 @@ struct AttnParams {
 };
 
 // ---- work list ---------------------------------------------------------------------------------
-// One workgroup.  items[] lists one 32-byte record per (request, q tile) pair -- {request, q tile, first
-// row of the request, its suffix length S, its reused length L} -- so that a workgroup of the attention
-// kernel learns everything about its piece of work from one load.  A request's heaviest (last) tile first.
+// One workgroup.  items[] lists one 32-byte record per (request, q tile) pair -- {request, first suffix row of
+// the tile, first row of the request in Q, its suffix length S, its reused length L, end row of the tile} -- so
+// that a workgroup of the attention kernel learns everything about its piece of work from one load.  A request's
+// heaviest (last) tile first.  The q tiles of a request are cut so that L + (first row of a tile) is a multiple of the
+// 64-key tile: the first tile is short when L is not, and every later tile ends exactly where a key tile ends, so
+// no workgroup streams a key tile for the sake of a few keys of round-up.
 constexpr int kItemInts = 8;
 __global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_off,
                                      const int32_t* __restrict__ matched_len, int pos_per_wg,
@@ -78,12 +81,13 @@ __global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_of
   __syncthreads();
   for (int base = 0; base < n_req; base += 1024) {
     const int r = base + threadIdx.x;
-    int nt = 0, S = 0, qb = 0, L = 0;
+    int nt = 0, S = 0, qb = 0, L = 0, head_rows = 0;   // head_rows: rows of the short first tile (0: none)
     if (r < n_req) {
       qb = q_off[r];
       S = q_off[r + 1] - qb;
       L = matched_len[r] > 0 ? matched_len[r] : 0;
-      nt = S > 0 ? (S + pos_per_wg - 1) / pos_per_wg : 0;
+      head_rows = min(S, (kBN - L % kBN) % kBN);
+      nt = S > 0 ? (head_rows > 0 ? 1 : 0) + (S - head_rows + pos_per_wg - 1) / pos_per_wg : 0;
     }
     sh[threadIdx.x] = nt;
     __syncthreads();
@@ -97,8 +101,17 @@ __global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_of
     for (int k = 0; k < nt; ++k) {
       if (start + k < max_items) {
         int4* rec = (int4*)(items + (size_t)kItemInts * (start + k));
-        rec[0] = make_int4(r, nt - 1 - k, qb, S);
-        rec[1] = make_int4(L, 0, 0, 0);
+        const int j = nt - 1 - k;   // tile index within the request
+        int row0, row1;
+        if (head_rows > 0 && j == 0) {
+          row0 = 0;
+          row1 = head_rows;
+        } else {
+          row0 = head_rows + (j - (head_rows > 0 ? 1 : 0)) * pos_per_wg;
+          row1 = min(S, row0 + pos_per_wg);
+        }
+        rec[0] = make_int4(r, row0, qb, S);
+        rec[1] = make_int4(L, row1, 0, 0);
       }
     }
     __syncthreads();
@@ -141,7 +154,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   // ---- which piece of work: XCD-aware decode (workgroup b runs on XCD b % 8) ----
   const int G = p.Hq / p.Hkv;
   const int n_hg = G / p.heads_per_wg;               // head groups per kv head
-  const int pos_per_wg = (kWaves / p.heads_per_wg) * kRowsPerWave;
   int item, kvh, hg;
   {
     const int b = blockIdx.x;
@@ -163,18 +175,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   // the record is read together with the item count (the grid bound keeps the index inside the list)
   const int4 rec0 = ((const int4*)(p.items + (size_t)kItemInts * item))[0];
   const int L = __builtin_amdgcn_readfirstlane(p.items[(size_t)kItemInts * item + 4]);
+  const int row1 = __builtin_amdgcn_readfirstlane(p.items[(size_t)kItemInts * item + 5]);   // end row of the q tile
   if (item >= *p.n_items) return;
   const int r = __builtin_amdgcn_readfirstlane(rec0.x);
-  const int qt = __builtin_amdgcn_readfirstlane(rec0.y);
+  const int row0 = __builtin_amdgcn_readfirstlane(rec0.y);                                  // first row of the q tile
   const int qbase = __builtin_amdgcn_readfirstlane(rec0.z);
   const int S = __builtin_amdgcn_readfirstlane(rec0.w);
   const int Ltot = L + S;
 
   const int head = kvh * G + hg * p.heads_per_wg + (wave % p.heads_per_wg);
-  const int pos0 = qt * pos_per_wg + (wave / p.heads_per_wg) * kRowsPerWave;  // first row of this wave
-  const int wg_pos_end = min(S, (qt + 1) * pos_per_wg);
-  const int n_tiles = (L + wg_pos_end + kBN - 1) / kBN;                      // 64-key tiles the workgroup streams
-  const int wave_key_end = pos0 < S ? L + min(S, pos0 + kRowsPerWave) : 0;    // this wave needs keys [0, wave_key_end)
+  const int pos0 = row0 + (wave / p.heads_per_wg) * kRowsPerWave;             // first row of this wave
+  const int n_tiles = (L + row1 + kBN - 1) / kBN;                             // 64-key tiles the workgroup streams
+  const int wave_key_end = pos0 < row1 ? L + min(row1, pos0 + kRowsPerWave) : 0;  // this wave needs keys [0, wave_key_end)
 
   // ---- Q fragments (B operand of S^T = K Q^T): lane holds query l32, d = 16 ks + 8 half .. +7
   // Rows are fetched whole (16 lanes x 16 B per row) into the wave's staging tile and picked up from there.
@@ -185,7 +197,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int rr = (lane >> 4) + 4 * i;
-      const int row = max(min(pos0 + rr, S - 1), 0);
+      const int row = min(pos0 + rr, S - 1);   // rows past the tile or the request are computed and dropped
       qv[i] = *(const u32x4*)((const __bf16*)p.q + ((size_t)(qbase + row) * p.Hq + head) * kD + c16 * 8);
     }
 #pragma unroll
@@ -404,7 +416,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
 
   // ---- normalise and store.  A lane holds query l32 with d = 32 a + 8 (e/4) + 4 half + e%4, i.e. sixteen 8-byte
   // pieces of one output row.  They go through the wave's staging tile and leave as whole 256-byte rows.
-  if (pos0 >= S) return;
+  if (pos0 >= row1) return;
   {
     const float lsum = sm.l_run + swap_halves(sm.l_run);
     const float inv = 1.0f / lsum;
@@ -430,7 +442,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
       const int rr = (lane >> 4) + 4 * i;   // row of this wave's tile
       const int pos = pos0 + rr;
       const u32x4 v = *(const u32x4*)(stage + rr * kD + ((c16 ^ (rr & 15)) << 3));
-      if (pos < S) *(u32x4*)((__bf16*)p.out + ((size_t)(qbase + pos) * p.Hq + head) * kD + c16 * 8) = v;
+      if (pos < row1) *(u32x4*)((__bf16*)p.out + ((size_t)(qbase + pos) * p.Hq + head) * kD + c16 * 8) = v;
     }
   }
 }
@@ -532,7 +544,7 @@ int64_t max_items_for(const skv_attn_desc* d, int32_t n_req, int64_t total_q_row
   if (d->dtype != SKV_BF16) return 0;
   const int hpw = heads_per_wg_for(d->n_q_heads / d->n_kv_heads);
   const int pos_per_wg = (kWaves / hpw) * kRowsPerWave;
-  return total_q_rows / pos_per_wg + n_req;
+  return total_q_rows / pos_per_wg + 2 * (int64_t)n_req;   // per request: a short first tile and a ragged last one
 }
 
 size_t zero_page_bytes(const skv_attn_desc* d) {
