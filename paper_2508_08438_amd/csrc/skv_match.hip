@@ -17,12 +17,15 @@ namespace {
 
 constexpr int kWave = 64;
 constexpr int kWavesPerWg = 4;
-constexpr int kSub = 8;                    // 64-token sub-windows per step
-constexpr int kStepBlocks = kSub * 4;      // 32 blocks (512 tokens) per step
+constexpr int kSub = 4;                    // 256-token sub-windows per step: one 16-byte vector (4 tokens) per lane each
+constexpr int kStepBlocks = kSub * 16;     // 64 blocks (1024 tokens) per step: one block per lane for metadata and page ids
+typedef int32_t tok4 __attribute__((ext_vector_type(4), aligned(4)));   // request offsets are token-, not 16-byte aligned
 
 __device__ inline uint64_t ballot64(bool p) { return __ballot(p); }
 
 __device__ inline int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+__device__ inline bool differ(tok4 p, tok4 q) { return ((p.x ^ q.x) | (p.y ^ q.y) | (p.z ^ q.z) | (p.w ^ q.w)) != 0; }
 
 // 64-bit hash of the 16-token block starting at x (all lanes return the same value)
 __device__ inline uint64_t hash_block(const int32_t* x, int lane) {
@@ -99,24 +102,35 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
     const int first = uniform(nd.first);
     const int nblk = uniform(nd.n_blocks);
     const int span = min(nblk, nb - j);  // blocks of this node the request can still cover
-    for (int c = 0; c < span && !stop; c += kStepBlocks) {
+    // The tokens and metadata of step c+1 are requested before step c is compared, so the walk down a long
+    // compressed node pays one memory latency per two steps instead of one per step.
+    tok4 a[kSub], b[kSub], a2[kSub], b2[kSub];
+    int m = 0, m2 = 0, pg = 0, pg2 = 0;   // per-block metadata word and page id of the lane's block
+    const int jn = j;   // request block that faces the node's first block
+    auto fetch = [&](int c, tok4* aa, tok4* bb, int& mm, int& pp) __attribute__((always_inline)) {
       const int cb = min(kStepBlocks, span - c);
       const int ntok = cb * 16;
-      const int32_t* tt = t.tok + (size_t)(first + c) * 16;
-      const int32_t* xx = x + (size_t)j * 16;
-      int32_t a[kSub], b[kSub];
+      const tok4* tt = (const tok4*)(t.tok + (size_t)(first + c) * 16);
+      const tok4* xx = (const tok4*)(x + (size_t)(jn + c) * 16);
+      const tok4 z = {0, 0, 0, 0};
 #pragma unroll
       for (int u = 0; u < kSub; ++u) {
-        const int i = u * kWave + lane;
-        a[u] = i < ntok ? xx[i] : 0;
-        b[u] = i < ntok ? tt[i] : 0;
+        const int i = u * kWave + lane;      // vector index: tokens 4 i .. 4 i + 3, block i / 4
+        aa[u] = 4 * i < ntok ? xx[i] : z;
+        bb[u] = 4 * i < ntok ? tt[i] : z;
       }
-      const int m = lane < cb ? t.meta[first + c + lane] : 0;
+      mm = lane < cb ? t.meta[first + c + lane] : 0;
+      pp = lane < cb ? t.page[first + c + lane] : 0;
+    };
+    if (span > 0) fetch(0, a, b, m, pg);
+    for (int c = 0; c < span && !stop; c += kStepBlocks) {
+      const int cb = min(kStepBlocks, span - c);
+      if (c + kStepBlocks < span) fetch(c + kStepBlocks, a2, b2, m2, pg2);
       int n_eq = cb;  // leading blocks whose tokens all agree
 #pragma unroll
       for (int u = kSub - 1; u >= 0; --u) {
-        const uint64_t ne = ballot64(a[u] != b[u]);
-        if (ne) n_eq = u * 4 + (__builtin_ctzll(ne) >> 4);
+        const uint64_t ne = ballot64(differ(a[u], b[u]));
+        if (ne) n_eq = u * 16 + (__builtin_ctzll(ne) >> 2);
       }
       // visibility rule: private (bit 31) entries only for their creator
       const uint64_t hidden = ballot64(m < 0 && (m & 0x7fffffff) != tenant);
@@ -124,7 +138,7 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
       const int take = min(n_eq, n_vis);
       if (lane < take) {
         const int blk = first + c + lane;
-        row[j + lane] = t.page[blk];
+        row[j + lane] = pg;
         uint32_t* ctr = t.ctr + (size_t)blk * SKV_CTR_STRIDE;
         atomicAdd(ctr, 1u);
         atomicOr(ctr + tword, tbit);
@@ -132,6 +146,10 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
       }
       j += take;
       if (take < cb) stop = true;
+#pragma unroll
+      for (int u = 0; u < kSub; ++u) { a[u] = a2[u]; b[u] = b2[u]; }
+      m = m2;
+      pg = pg2;
     }
     node = child;
   }
@@ -237,19 +255,20 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_copies_kernel(
         const int ntok = cb * 16;
         const int32_t* tt = t.tok + (size_t)(first + c) * 16;
         const int32_t* xx = x + (size_t)j * 16;
-        int32_t a[kSub], b[kSub];
+        tok4 a[kSub], b[kSub];
+        const tok4 z = {0, 0, 0, 0};
 #pragma unroll
         for (int u = 0; u < kSub; ++u) {
-          const int i = u * kWave + lane;
-          a[u] = i < ntok ? xx[i] : 0;
-          b[u] = i < ntok ? tt[i] : 0;
+          const int i = u * kWave + lane;    // vector index: tokens 4 i .. 4 i + 3, block i / 4
+          a[u] = 4 * i < ntok ? ((const tok4*)xx)[i] : z;
+          b[u] = 4 * i < ntok ? ((const tok4*)tt)[i] : z;
         }
         const int m = lane < cb ? t.meta[first + c + lane] : 0;
         int n_eq = cb;
 #pragma unroll
         for (int u = kSub - 1; u >= 0; --u) {
-          const uint64_t ne = ballot64(a[u] != b[u]);
-          if (ne) n_eq = u * 4 + (__builtin_ctzll(ne) >> 4);
+          const uint64_t ne = ballot64(differ(a[u], b[u]));
+          if (ne) n_eq = u * 16 + (__builtin_ctzll(ne) >> 2);
         }
         const uint64_t hidden = ballot64(m < 0 && (m & 0x7fffffff) != tenant);
         const int n_vis = hidden ? __builtin_ctzll(hidden) : cb;
