@@ -118,6 +118,7 @@ class Tree:
 
     def __init__(self, handle, slab):
         self.handle, self.slab = handle, slab
+        self._destroy = lib().skv_tree_destroy   # bound now: module globals may be gone when __del__ runs at exit
 
     def info(self):
         a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
@@ -126,7 +127,7 @@ class Tree:
 
     def __del__(self):
         if getattr(self, "handle", None):
-            lib().skv_tree_destroy(self.handle)
+            self._destroy(self.handle)
             self.handle = None
 
 
