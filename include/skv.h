@@ -15,8 +15,9 @@
  *  - The library never allocates or frees device memory.  Every device buffer, including
  *    the tree slab and the attention workspace, belongs to the caller and must stay valid
  *    until the work enqueued on `stream` has finished.
- *  - Calls only enqueue work on `stream` and return; they do not synchronise, except
- *    skv_tree_build, which returns after its uploads have completed.
+ *  - Calls only enqueue work on `stream` and return; they do not synchronise, except the
+ *    host-driven structure changes skv_tree_build, skv_tree_insert, skv_evict and skv_tree_compact,
+ *    which return after their uploads have completed.
  *  - Every function returns SKV_OK (0) or a negative error code; nothing is enqueued when
  *    an error is returned.  Arguments that live on the device (offsets, tenants, page ids)
  *    cannot be validated by the host: kernels clamp or skip values that are out of range
@@ -91,7 +92,7 @@ int skv_tree_build(const skv_tree_desc* desc, void* d_slab, size_t bytes, void* 
                    skv_tree** out);
 
 /* Insert after a prefill (Section 4.3.1 Insert: new KV blocks are appended along the request's path;
- * Section 4.2.1: every new block starts private, with the requester as creator_id).  All arrays are HOST
+ * Section 4.1 and Section 5: every new block starts private, with the requester as creator_id).  All arrays are HOST
  * arrays.  For request r (tokens req_tokens[req_off[r] .. req_off[r+1]), tenant req_tenant[r]) the full
  * 16-token blocks that the tree does not hold yet are appended below the point where the request's token
  * path leaves the tree (splitting a compressed node when that point lies inside it), private to the tenant.
@@ -179,8 +180,8 @@ int skv_match(skv_tree* tree, int32_t n_req, const int32_t* d_req_off, const int
  * n_in_blocks entries; blocks that repeat an already cached block-prefix read 0. */
 int skv_counters_read(skv_tree* tree, uint32_t* d_hit, uint32_t* d_ucnt, void* stream);
 
-/* Clear the current window: zero every block's hit counter and tenant set (previous-window counters and
- * the predicate streak are kept). */
+/* Clear the current window (Section 4.2.2: the access monitor keeps its counters over a rolling window):
+ * zero every block's hit counter and tenant set; previous-window counters and the predicate streak are kept. */
 int skv_counters_reset(skv_tree* tree, void* stream);
 
 /* Safeguard policy (Section 4.2.2 and Section 6).  RDR = u_cnt / hit_cur is compared with
@@ -228,7 +229,8 @@ typedef struct {
   int32_t n_kv_heads; /* divides n_q_heads; query head h uses kv head h / (n_q_heads/n_kv_heads) */
   int32_t head_dim;   /* SKV_BF16: 128;  SKV_F32: 64 or 128 */
   int32_t dtype;      /* SKV_F32 or SKV_BF16: type of Q, K, V, the pools and the output */
-  float scale;        /* softmax scale, normally 1/sqrt(head_dim) */
+  float scale;        /* softmax scale; a value <= 0 (or not finite) selects 1/sqrt(head_dim), the scaled
+                         dot-product attention of Section 2.1 */
 } skv_attn_desc;
 
 /* Gather the reused pages (Section 4.3.2: the lookup reads the required KV blocks directly from
@@ -262,7 +264,8 @@ int skv_prefill_attn_workspace_size(const skv_attn_desc* desc, int32_t n_req, in
 /* Causal GQA prefill attention of the uncached suffixes (Section 2.1).  For request r, suffix
  * position i in [0, S_r), S_r = d_q_off[r+1] - d_q_off[r], query head h:
  *   O[q_off[r]+i, h] = softmax_j(scale * q[q_off[r]+i, h] . k_j) . v_j
- * over j in [0, L_r + i]: first the L_r = d_matched_len[r] reused positions, read from the
+ * over j in [0, L_r + i]: first the L_r = d_matched_len[r] reused positions (whole blocks: a value that is
+ * not a multiple of 16 is rounded down, as in skv_gather_kv), read from the
  * pools through d_page_table[r*max_blocks + j/16] at slot j%16, then the request's own new
  * positions 0..i from d_knew / d_vnew (rows q_off[r] + (j - L_r)).
  * d_q, d_out: [total rows][n_q_heads][head_dim]; d_knew, d_vnew: [total rows][n_kv_heads][head_dim].

@@ -109,8 +109,7 @@ def _stream(stream):
 
 def attn_desc(n_q_heads, n_kv_heads, head_dim, dtype, scale=None) -> AttnDesc:
     code = {torch.float32: SKV_F32, torch.bfloat16: SKV_BF16, "f32": SKV_F32, "bf16": SKV_BF16}[dtype]
-    return AttnDesc(n_q_heads, n_kv_heads, head_dim, code,
-                    float(scale if scale is not None else head_dim ** -0.5))
+    return AttnDesc(n_q_heads, n_kv_heads, head_dim, code, float(scale if scale is not None else 0.0))
 
 
 class Tree:

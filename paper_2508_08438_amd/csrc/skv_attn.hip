@@ -85,7 +85,7 @@ __global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_of
     if (r < n_req) {
       qb = q_off[r];
       S = q_off[r + 1] - qb;
-      L = matched_len[r] > 0 ? matched_len[r] : 0;
+      L = matched_len[r] > 0 ? matched_len[r] & ~(SKV_BLOCK_TOKENS - 1) : 0;   // whole blocks only
       head_rows = min(S, (kBN - L % kBN) % kBN);
       nt = S > 0 ? (head_rows > 0 ? 1 : 0) + (S - head_rows + pos_per_wg - 1) / pos_per_wg : 0;
     }
@@ -464,7 +464,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p, int64_t max_
   const int r = lo;
   const int qbase = p.q_off[r];
   const int i = (int)(tok - qbase);
-  const int L = p.matched_len[r] > 0 ? p.matched_len[r] : 0;
+  const int L = p.matched_len[r] > 0 ? p.matched_len[r] & ~(SKV_BLOCK_TOKENS - 1) : 0;   // whole blocks only
   const int n_keys = L + i + 1;
   const int hk = h / (p.Hq / p.Hkv);
   const float* q = (const float*)p.q + ((size_t)tok * p.Hq + h) * D;
@@ -562,25 +562,25 @@ extern "C" int skv_prefill_attn_workspace_size(const skv_attn_desc* desc, int32_
   return SKV_OK;
 }
 
-extern "C" int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const void* d_q,
-                                const void* d_knew, const void* d_vnew, const int32_t* d_q_off,
-                                int64_t total_q_rows, const void* d_kpool, const void* d_vpool,
-                                int32_t n_pages, const int32_t* d_matched_len,
-                                const int32_t* d_page_table, int32_t max_blocks, void* d_out,
-                                void* d_workspace, size_t workspace_bytes, void* stream) {
-  int rc = check_attn(desc);
-  if (rc) return rc;
-  if (n_req < 0 || total_q_rows < 0 || n_pages < 0 || max_blocks < 0) return SKV_EINVAL;
-  if (n_req == 0 || total_q_rows == 0) return SKV_OK;
+// Host-checkable argument errors common to both entry points.
+static int check_attn_buffers(const void* d_q, const void* d_knew, const void* d_vnew, const int32_t* d_q_off,
+                              const void* d_kpool, const void* d_vpool, const int32_t* d_matched_len,
+                              const int32_t* d_page_table, int32_t max_blocks, const void* d_out) {
   if (!d_q || !d_knew || !d_vnew || !d_q_off || !d_matched_len || !d_out) return SKV_EINVAL;
   if (max_blocks > 0 && (!d_page_table || !d_kpool || !d_vpool)) return SKV_EINVAL;
   if (((uintptr_t)d_q | (uintptr_t)d_knew | (uintptr_t)d_vnew | (uintptr_t)d_kpool | (uintptr_t)d_vpool |
        (uintptr_t)d_out) & 15)
     return SKV_EINVAL;
-  size_t need = 0;
-  skv_prefill_attn_workspace_size(desc, n_req, total_q_rows, &need);
-  if (!d_workspace || workspace_bytes < need) return SKV_ENOMEM;
-  if ((uintptr_t)d_workspace & 15) return SKV_EINVAL;
+  return SKV_OK;
+}
+
+// Shared by both entry points: enqueues the schedule kernel and the attention kernel on checked arguments.
+static int prefill_attn_enqueue(const skv_attn_desc* desc, int32_t n_req, const void* d_q,
+                                const void* d_knew, const void* d_vnew, const int32_t* d_q_off,
+                                int64_t total_q_rows, const void* d_kpool, const void* d_vpool,
+                                int32_t n_pages, const int32_t* d_matched_len,
+                                const int32_t* d_page_table, int32_t max_blocks, void* d_out,
+                                void* d_workspace, void* stream) {
   hipStream_t st = (hipStream_t)stream;
 
   AttnParams p;
@@ -592,7 +592,7 @@ extern "C" int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const 
   p.n_req = n_req; p.max_blocks = max_blocks; p.n_pages = n_pages;
   p.Hq = desc->n_q_heads; p.Hkv = desc->n_kv_heads;
   p.heads_per_wg = heads_per_wg_for(desc->n_q_heads / desc->n_kv_heads);
-  p.scale = desc->scale;
+  p.scale = skv_softmax_scale(desc);
 
   if (desc->dtype == SKV_F32) {
     const int64_t rows = total_q_rows * desc->n_q_heads;
@@ -617,4 +617,25 @@ extern "C" int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const 
   attn_bf16_kernel<<<(int)grid, kThreads, 0, st>>>(p);
   SKV_HIP(hipGetLastError());
   return SKV_OK;
+}
+
+extern "C" int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const void* d_q,
+                                const void* d_knew, const void* d_vnew, const int32_t* d_q_off,
+                                int64_t total_q_rows, const void* d_kpool, const void* d_vpool,
+                                int32_t n_pages, const int32_t* d_matched_len,
+                                const int32_t* d_page_table, int32_t max_blocks, void* d_out,
+                                void* d_workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_attn(desc);
+  if (rc) return rc;
+  if (n_req < 0 || total_q_rows < 0 || n_pages < 0 || max_blocks < 0) return SKV_EINVAL;
+  if (n_req == 0 || total_q_rows == 0) return SKV_OK;
+  rc = check_attn_buffers(d_q, d_knew, d_vnew, d_q_off, d_kpool, d_vpool, d_matched_len, d_page_table, max_blocks,
+                          d_out);
+  if (rc) return rc;
+  size_t need = 0;
+  skv_prefill_attn_workspace_size(desc, n_req, total_q_rows, &need);
+  if (!d_workspace || workspace_bytes < need) return SKV_ENOMEM;
+  if ((uintptr_t)d_workspace & 15) return SKV_EINVAL;
+  return prefill_attn_enqueue(desc, n_req, d_q, d_knew, d_vnew, d_q_off, total_q_rows, d_kpool, d_vpool, n_pages,
+                              d_matched_len, d_page_table, max_blocks, d_out, d_workspace, stream);
 }

@@ -373,7 +373,7 @@ extern "C" int skv_decode_attn(const skv_attn_desc* desc, int32_t n_req, const v
   p.part_o = (float*)((char*)p.part_l + skv_align256(states * sizeof(float)));
   p.n_req = n_req; p.max_blocks = max_blocks; p.n_pages = n_pages;
   p.Hq = desc->n_q_heads; p.Hkv = desc->n_kv_heads; p.G = (int)G;
-  p.n_splits = ns; p.tiles_per_split = tps; p.scale = desc->scale;
+  p.n_splits = ns; p.tiles_per_split = tps; p.scale = skv_softmax_scale(desc);
   zero_fill_kernel<<<8, 256, 0, st>>>((uint4*)ws, (int)(zero_bytes(desc) / 16));
   decode_attn_kernel<<<(int)grid, kThreads, 0, st>>>(p);
   SKV_HIP(hipGetLastError());

@@ -3,6 +3,7 @@
 #define SKV_INTERNAL_H
 
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 #include "skv.h"
@@ -81,5 +82,13 @@ void skv_set_hip_error(int e);
   } while (0)
 
 static inline size_t skv_align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Softmax scale of an attention description: the caller's value when it is a positive finite number,
+// otherwise 1/sqrt(head_dim) (scaled dot-product attention, SafeKV Section 2.1).
+static inline float skv_softmax_scale(const skv_attn_desc* d) {
+  const float s = d->scale;
+  if (s > 0.f && s < 3.0e38f) return s;
+  return 1.0f / sqrtf((float)d->head_dim);
+}
 
 #endif
