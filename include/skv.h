@@ -281,6 +281,22 @@ int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const void* d_q, 
                      const int32_t* d_matched_len, const int32_t* d_page_table, int32_t max_blocks,
                      void* d_out, void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* skv_prefill_attn for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * skv_prefill_attn without the workspace: the work list and the page of zeros live in a device array built
+ * into the library (SKV_STATIC_SCRATCH_BYTES per GPU, held until the process ends), whose address on the
+ * current device is looked up on the first call there.  The call allocates and frees nothing.
+ * SKV_ERANGE when skv_prefill_attn_workspace_size for (n_req, total_q_rows) exceeds SKV_STATIC_SCRATCH_BYTES
+ * (bf16 with 4 query heads per kv head: about 8 million uncached tokens per batch).
+ * All calls on one GPU share the array, whichever stream they use: calls that overlap on a GPU race; calls
+ * on one stream, or ordered by events, are safe (each call rewrites everything it reads). */
+#define SKV_STATIC_SCRATCH_BYTES (4u << 20)
+int skv_prefill_attn_static(const skv_attn_desc* desc, int32_t n_req, const void* d_q, const void* d_knew,
+                            const void* d_vnew, const int32_t* d_q_off, int64_t total_q_rows,
+                            const void* d_kpool, const void* d_vpool, int32_t n_pages,
+                            const int32_t* d_matched_len, const int32_t* d_page_table, int32_t max_blocks,
+                            void* d_out, void* stream);
+
 /* Decode-step attention (Section 2.1: at every decode step the new token attends to the cached K/V of all
  * earlier tokens).  For request r, d_q holds one query row per query head ([n_req][n_q_heads][head_dim]) and
  * d_ctx_len[r] the number of cached tokens it attends to (the current token's K/V included, already written

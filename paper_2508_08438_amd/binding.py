@@ -21,7 +21,7 @@ EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tre
            "skv_tree_info", "skv_tree_destroy", "skv_match", "skv_counters_read",
            "skv_counters_reset", "skv_window_roll", "skv_promote", "skv_block_state_read", "skv_suffix_offsets", "skv_gather_kv",
            "skv_scatter_kv", "skv_decode_attn_workspace_size", "skv_decode_attn",
-           "skv_prefill_attn_workspace_size", "skv_prefill_attn"]
+           "skv_prefill_attn_workspace_size", "skv_prefill_attn", "skv_prefill_attn_static"]
 
 
 class SkvError(RuntimeError):
@@ -86,6 +86,8 @@ def lib():
         l.skv_prefill_attn_workspace_size.argtypes = [C.POINTER(AttnDesc), i32, i64, C.POINTER(C.c_size_t)]
         l.skv_prefill_attn.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp,
                                        i32, vp, vp, C.c_size_t, vp]
+        l.skv_prefill_attn_static.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp,
+                                              i32, vp, vp]
         _lib = l
     return _lib
 
@@ -295,6 +297,17 @@ def skv_prefill_attn(desc: AttnDesc, q, knew, vnew, q_off, kpool, vpool, matched
                                   _dptr(page_table), max_blocks, _dptr(out), _dptr(workspace),
                                   workspace.numel() * workspace.element_size(), _stream(stream)),
            "skv_prefill_attn")
+
+
+def skv_prefill_attn_static(desc: AttnDesc, q, knew, vnew, q_off, kpool, vpool, matched_len, page_table, max_blocks,
+                            out, stream=None):
+    n_req = matched_len.numel()
+    total = q.shape[0]
+    assert out.shape == q.shape and knew.shape[0] >= total and vnew.shape[0] >= total
+    _check(lib().skv_prefill_attn_static(C.byref(desc), n_req, _dptr(q), _dptr(knew), _dptr(vnew), _dptr(q_off),
+                                         total, _dptr(kpool), _dptr(vpool), kpool.shape[0], _dptr(matched_len),
+                                         _dptr(page_table), max_blocks, _dptr(out), _stream(stream)),
+           "skv_prefill_attn_static")
 
 
 def skv_decode_attn_workspace_size(desc: AttnDesc, n_req, max_blocks) -> int:

@@ -17,6 +17,8 @@
 // the P^T accumulator registers are already in the B-operand layout of the second product;
 // V^T fragments come from the LDS transpose load.
 // fp32 path: one wavefront per output row, plain fp32 arithmetic (correctness configuration).
+#include <atomic>
+
 #include "skv_internal.h"
 
 namespace {
@@ -638,4 +640,54 @@ extern "C" int skv_prefill_attn(const skv_attn_desc* desc, int32_t n_req, const 
   if ((uintptr_t)d_workspace & 15) return SKV_EINVAL;
   return prefill_attn_enqueue(desc, n_req, d_q, d_knew, d_vnew, d_q_off, total_q_rows, d_kpool, d_vpool, n_pages,
                               d_matched_len, d_page_table, max_blocks, d_out, d_workspace, stream);
+}
+
+// ---- the same call for callers that cannot allocate ---------------------------------------------
+// The work list and the page of zeros live in a file-scope device array instead of a caller workspace.  Every GPU
+// the library runs on holds its own copy of the array at its own address, looked up once per device.
+static __device__ __align__(256) unsigned char scratch[SKV_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];   // device address of `scratch` per device, null until looked up
+
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  SKV_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SKV_ERANGE;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    // the array's name is only a host-side stand-in; this is its address on the current device
+    SKV_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return SKV_EHIP;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // racing first calls store the same value
+  }
+  *out = ptr;
+  return SKV_OK;
+}
+}  // namespace
+
+extern "C" int skv_prefill_attn_static(const skv_attn_desc* desc, int32_t n_req, const void* d_q,
+                                       const void* d_knew, const void* d_vnew, const int32_t* d_q_off,
+                                       int64_t total_q_rows, const void* d_kpool, const void* d_vpool,
+                                       int32_t n_pages, const int32_t* d_matched_len,
+                                       const int32_t* d_page_table, int32_t max_blocks, void* d_out,
+                                       void* stream) {
+  int rc = check_attn(desc);
+  if (rc) return rc;
+  if (n_req < 0 || total_q_rows < 0 || n_pages < 0 || max_blocks < 0) return SKV_EINVAL;
+  if (n_req == 0 || total_q_rows == 0) return SKV_OK;
+  rc = check_attn_buffers(d_q, d_knew, d_vnew, d_q_off, d_kpool, d_vpool, d_matched_len, d_page_table, max_blocks,
+                          d_out);
+  if (rc) return rc;
+  size_t need = 0;
+  skv_prefill_attn_workspace_size(desc, n_req, total_q_rows, &need);
+  if (need > (size_t)SKV_STATIC_SCRATCH_BYTES) return SKV_ERANGE;   // batch too large for the built-in scratch
+  void* ws = nullptr;
+  rc = scratch_of_current_device(&ws);
+  if (rc) return rc;
+  // the schedule kernel rewrites the item count, the page of zeros and every record it hands out on each call,
+  // so nothing of the previous call's contents is read
+  return prefill_attn_enqueue(desc, n_req, d_q, d_knew, d_vnew, d_q_off, total_q_rows, d_kpool, d_vpool, n_pages,
+                              d_matched_len, d_page_table, max_blocks, d_out, ws, stream);
 }

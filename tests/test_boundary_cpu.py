@@ -150,3 +150,18 @@ def test_insert_evict_scatter_decode_argument_checks(skv):
     args = [None, None, None, 4, None, None, 16, None, None, 0, None]
     assert l.skv_decode_attn(C.byref(good), 4, *args) == -1          # null tensors
     assert l.skv_decode_attn(C.byref(good), 0, *args) == 0           # empty batch
+
+
+def test_static_scratch_attention_rejects_oversized_batches_before_touching_the_device(skv):
+    l = skv.lib()
+    good = skv.attn_desc(32, 8, 128, "bf16")
+    n = C.c_size_t()
+    rows = 1 << 28
+    assert l.skv_prefill_attn_workspace_size(C.byref(good), 4, rows, C.byref(n)) == 0 and n.value > (4 << 20)
+    fake = C.c_void_p(1 << 20)   # aligned, never dereferenced: the size check fails first
+    args = [fake, fake, fake, fake, rows, fake, fake, 8, fake, fake, 4, fake, None]
+    assert l.skv_prefill_attn_static(C.byref(good), 4, *args) == -3
+    assert l.skv_prefill_attn_static(C.byref(good), 0, *args) == 0           # empty batch
+    args[0] = None
+    assert l.skv_prefill_attn_static(C.byref(good), 4, *args) == -1          # null tensor
+    assert l.skv_prefill_attn_static(None, 4, *args) == -1
