@@ -35,7 +35,7 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr int kD = 128;          // head dim of the bf16 kernel
 constexpr int kBN = 64;          // keys per LDS tile
-constexpr int kKStages = 2;      // LDS stages of K
+constexpr int kKStages = 3;      // LDS stages of K (scores run one sub-tile ahead of the output update)
 constexpr int kVStages = 2;      // LDS stages of V
 constexpr float kRescaleLog2 = 8.f;  // move the softmax reference when a row maximum exceeds it by 2^8
 constexpr int kRowsPerWave = 32; // query rows per wavefront
@@ -132,11 +132,39 @@ __device__ inline float swap_halves(float x) {
   asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
   return (threadIdx.x & 32) ? a : b;
 }
+// max / sum of a value and the one 32 lanes away: after the swap `a` holds the lower half's value in both halves
+// and `b` the upper half's, so no lane select is needed
+__device__ inline float max_halves(float x) {
+  float a = x, b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  return fmaxf(a, b);
+}
 
-struct Softmax {
-  float m_ref;   // reference maximum the exponentials are taken against (raw score units)
-  float l_run;   // running row sum over this lane-half's keys
-};
+// LDS fragment reads as inline assembly, with their waits placed by hand.  The compiler puts a full
+// s_waitcnt vmcnt(0) in front of LDS reads it cannot tell apart from the targets of the direct-to-LDS loads in
+// flight, which would stall every tile on the copies of the next one; the tile barrier already orders those
+// copies against the reads.  The LDS returns data in issue order, so "at most n operations outstanding" means that
+// everything issued before the n youngest reads has arrived.  A wait takes the registers it guards as in/out
+// operands: their consumers then depend on it and cannot be moved in front of it.
+__device__ __forceinline__ uint32_t lds_addr(const void* ptr) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)ptr;
+}
+__device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr, int byte_off) {
+  bf16x8 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "i"(byte_off));
+  return v;
+}
+__device__ __forceinline__ s16x4 lds_read_tr16_b64(uint32_t addr, int byte_off) {
+  s16x4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "i"(byte_off));
+  return v;
+}
+__device__ __forceinline__ void lds_wait(int n, bf16x8& a) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "i"(n));
+}
+__device__ __forceinline__ void lds_wait(int n, bf16x8& a, bf16x8& b, bf16x8& c, bf16x8& d) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "i"(n));
+}
 
 __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   __shared__ __attribute__((aligned(16))) __bf16 smem[kKStages * kTile + kVStages * kTile +
@@ -191,7 +219,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   const int wave_key_end = pos0 < row1 ? L + min(row1, pos0 + kRowsPerWave) : 0;  // this wave needs keys [0, wave_key_end)
 
   // ---- Q fragments (B operand of S^T = K Q^T): lane holds query l32, d = 16 ks + 8 half .. +7
-  // Rows are fetched whole (16 lanes x 16 B per row) into the wave's staging tile and picked up from there.
+  // Rows are fetched whole (16 lanes x 16 B per row), multiplied once by scale * log2(e) -- the scores then leave
+  // the matrix core in the units of exp2 -- and picked up from the wave's staging tile.
+  const float c = p.scale * kLog2e;
   bf16x8 qf[8];
   {
     const int c16 = lane & 15;
@@ -205,7 +235,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int rr = (lane >> 4) + 4 * i;
-      *(u32x4*)(stage + rr * kD + ((c16 ^ (rr & 15)) << 3)) = qv[i];
+      u32x4 w;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t x = qv[i][k];
+        f32x2 pr = {__builtin_bit_cast(float, x << 16) * c, __builtin_bit_cast(float, x & 0xffff0000u) * c};
+        w[k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+      }
+      *(u32x4*)(stage + rr * kD + ((c16 ^ (rr & 15)) << 3)) = w;
     }
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8*)(stage + l32 * kD + (((2 * ks + half) ^ (l32 & 15)) << 3));
@@ -216,21 +253,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   for (int a = 0; a < 4; ++a)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[a][e] = 0.f;
-  Softmax sm{-INFINITY, 0.f};
-  const float c = p.scale * kLog2e;
-  const float thr = kRescaleLog2 / c;  // raw-score distance above the reference that forces a rescale
 
   // ---- global -> LDS, without a stop in registers ----
   // A tile is four 16-key groups; a group is one page of the pool or 16 consecutive new rows.  Each wavefront
-  // moves two K and two V segments of a tile (segments w and w + 8: keys 4w.. and 32 + 4w..) with direct-to-LDS
-  // loads: lane i fetches chunk 4 (i / 16) + i % 4 of key (i / 4) % 4 of the segment and the hardware puts it at slot i.
+  // moves two segments of a tile (segments w and w + 8: keys 4w.. and 32 + 4w..) with direct-to-LDS loads: lane i
+  // fetches chunk 4 (i / 16) + i % 4 of key (i / 4) % 4 of the segment and the hardware puts it at slot i.
   const unsigned row_bytes = (unsigned)p.Hkv * kD * 2u;
   const int t_row = (wave & 3) * 4 + ((lane >> 2) & 3);      // row of the 16-key group this lane fetches
   const unsigned t_col = (unsigned)((lane >> 4) * 4 + (lane & 3)) * 16u;
   const unsigned t_off = (unsigned)t_row * row_bytes + t_col;
-  // Group base addresses, one 16-key group per lane for the next 64 groups (16 tiles): a pool page, 16 new rows,
+  // Group base addresses, one 16-key group per lane for 64 groups (16 tiles, a "window"): a pool page, 16 new rows,
   // or the page of zeros when the group has no data (past the end of the sequence, or a page id outside the pool).
-  // A tile's bases are read with lane broadcasts.  Window w is fetched one iteration before its first use.
+  // A tile's bases are read with lane broadcasts.  Two consecutive windows are held; K tiles run one tile ahead of
+  // V tiles, so for one iteration in sixteen K reads the later window while V still reads the earlier one.
   auto fetch_window = [&](int w, uint64_t& ak, uint64_t& av) __attribute__((always_inline)) {
     const int gi = w * 64 + lane;
     const int key0 = gi * SKV_BLOCK_TOKENS;
@@ -257,29 +292,34 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
     const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), idx);
     return (const __attribute__((address_space(1))) char*)(((uint64_t)hi << 32) | lo);   // global, not flat
   };
-  uint64_t ak_cur, av_cur, ak_nxt = 0, av_nxt = 0;
+  uint64_t ak_cur, av_cur, ak_nxt, av_nxt;
+  int win = 0;                       // window held in *_cur; *_nxt holds window win + 1
   fetch_window(0, ak_cur, av_cur);
+  fetch_window(1, ak_nxt, av_nxt);
   typedef __attribute__((address_space(3))) void lds_void;
-  auto load_tile = [&](int kt) __attribute__((always_inline)) {
-    const int key_base = kt * kBN;
-    __bf16* const kdst = Ks + (kt % kKStages) * kTile + wave * kSeg;
-    __bf16* const vdst = Vs + (kt % kVStages) * kTile + wave * kSeg;
+  // one pool (K or V) of tile t into an LDS stage; `bases` holds the window of tile t
+  auto load_half_tile = [&](uint64_t bases, int t, __bf16* dst_stage) __attribute__((always_inline)) {
+    const int key_base = t * kBN;
+    __bf16* const dst = dst_stage + wave * kSeg;
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc) {
       const int g = (wave >> 2) + 2 * cc;                    // 16-key group of segment wave + 8 cc
-      const int idx = ((kt & 15) << 2) + g;
-      const auto kb = lane_bcast(ak_cur, idx);
-      const auto vb = lane_bcast(av_cur, idx);
+      const int idx = ((t & 15) << 2) + g;
+      const auto gb = lane_bcast(bases, idx);
       unsigned off = t_off;
       if (key_base + kBN > Ltot) {  // the sequence ends inside this tile: rows past its end re-read its last row,
         const int n_valid = Ltot - (key_base + g * 16);  // finite values that the causal mask keeps out
         if (n_valid > 0 && n_valid < 16) off = (unsigned)min(t_row, n_valid - 1) * row_bytes + t_col;
       }
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kb + off),
-                                       (lds_void*)(kdst + cc * 8 * kSeg), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vb + off),
-                                       (lds_void*)(vdst + cc * 8 * kSeg), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gb + off),
+                                       (lds_void*)(dst + cc * 8 * kSeg), 16, 0, 0);
     }
+  };
+  auto load_k_tile = [&](int t, int stage_idx) __attribute__((always_inline)) {
+    load_half_tile((t >> 4) == win ? ak_cur : ak_nxt, t, Ks + stage_idx * kTile);
+  };
+  auto load_v_tile = [&](int t) __attribute__((always_inline)) {
+    load_half_tile((t >> 4) == win ? av_cur : av_nxt, t, Vs + (t & 1) * kTile);
   };
   // a wave's direct loads are in LDS once its vector-memory counter has drained; the barrier then publishes them
   auto tile_barrier = [&]() __attribute__((always_inline)) {
@@ -287,13 +327,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
     __syncthreads();
   };
 
-  // ---- the phases of a tile ----
-  // LDS fragment reads run eight fragments ahead of the MFMAs that consume them (a fragment register
-  // is refilled as soon as its MFMA has been issued), and the first V fragments are requested before
-  // the softmax, so that LDS latency hides behind matrix-core and vector work.
-  f32x16 s[2];   // S^T of the current tile: [64 keys][32 queries] as two 32x32 tiles
-  bf16x8 pb[4];  // P^T as B operands, one per 16-key group
-  bf16x8 fr[8];  // fragment ring: K fragments during QK, V^T fragments during PV
+  // ---- the steps of the pipeline ----
+  // Work advances in 32-key sub-tiles (half an LDS tile).  The scores of sub-tile u + 1 are put on the matrix core
+  // BEFORE the softmax of sub-tile u is computed on the vector ALU, and the output update with sub-tile u follows it:
+  // neighbouring matrix and vector blocks of the instruction stream never depend on each other, so they run
+  // side by side.  Two score accumulators alternate.
+  f32x16 s[2];      // S^T of two consecutive sub-tiles: [32 keys][32 queries], already minus the softmax reference
+  f32x16 negm;      // minus the reference, in every element: C operand of the first score MFMA of a sub-tile
+  bf16x8 pb[2];     // P^T as B operands, one per 16-key group of the sub-tile
+  bf16x8 kfr[4];    // K fragment ring: runs four fragments ahead, across sub-tiles
+  bf16x8 vfr[4];    // V^T fragment ring
+  float m_ref = 0.f;   // reference the stored scores are relative to (log2 units), per query
+  float l_run = 0.f;   // running row sum over this lane-half's keys
+#pragma unroll
+  for (int e = 0; e < 16; ++e) negm[e] = s[0][e] = s[1][e] = 0.f;
   // K fragment (ks, mt): lane (l32, half) wants key l32 + 32 mt, chunk 2 ks + half.  In bf16 elements:
   //   segment (l32 / 4 + 8 mt) * kSeg + key-in-segment (l32 % 4) * 32 + (ks / 2) * 128 + (2 (ks % 2) + half) * 8
   const int k_lane = (l32 >> 2) * kSeg + (l32 & 3) * 32 + half * 8;
@@ -304,123 +351,174 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   // 16 g16 + 4 half + (lane % 16) / 4 (segment 4 g16 + half, second load two segments on) and its 8 bytes are piece
   // lane % 2 of chunk 4 a + 2 ((lane / 16) % 2) + (lane % 4) / 2.
   const int v_lane = half * kSeg + ((lane & 15) >> 2) * 32 + (2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) * 8 + 4 * (lane & 1);
-  auto k_frag = [&](const __bf16* kb, int j) __attribute__((always_inline)) {   // fragment j = (ks, mt) = (j / 2, j % 2)
-    return *(const bf16x8*)(kb + (j & 1) * 8 * kSeg + (j >> 2) * 128 + ((j >> 1) & 1) * 16);
+  // fragment addresses are LDS byte addresses: a per-lane base plus constants that fit the offset field
+  auto k_frag = [&](uint32_t kb, int ks) __attribute__((always_inline)) {   // kb: stage + k_lane + mt * 8 kSeg
+    return lds_read_b128(kb, ((ks >> 1) * 128 + (ks & 1) * 16) * 2);
   };
-  auto v_frag = [&](const __bf16* vb, int j) __attribute__((always_inline)) {   // fragment j = (g16, a) = (j / 4, j % 4)
-    const __bf16* src = vb + (j >> 2) * 4 * kSeg + (j & 3) * 128;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + 2 * kSeg));
+  auto v_frag = [&](uint32_t vb, int j) __attribute__((always_inline)) {   // vb: stage + v_lane + h * 8 kSeg; j = (g, a)
+    const int off = ((j >> 2) * 4 * kSeg + (j & 3) * 128) * 2;
+    const s16x4 lo = lds_read_tr16_b64(vb, off);
+    const s16x4 hi = lds_read_tr16_b64(vb, off + 2 * kSeg * 2);
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
-  // S^T = K Q^T, then the causal mask on tiles that reach past the first row's limit
-  auto qk = [&](int kt) __attribute__((always_inline)) {
-    const __bf16* kb = Ks + (kt % kKStages) * kTile + k_lane;
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // Scores of one sub-tile: dst = K Q^T - reference.  The ring holds fragments 0..3 of this sub-tile, requested during
+  // the previous call; it is refilled with fragments 4..7 and then with fragments 0..3 of the sub-tile that follows
+  // (kb_next).  younger: LDS reads issued since that previous call (the V^T prefetch of this step).
+  auto qk = [&](int younger, uint32_t kb, uint32_t kb_next, f32x16& dst) __attribute__((always_inline)) {
+    lds_wait(younger, kfr[0], kfr[1], kfr[2], kfr[3]);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) fr[j] = k_frag(kb, j);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int ks = j >> 1, mt = j & 1;
-      s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 7], qf[ks], ks == 0 ? zero : s[mt], 0, 0, 0);
-      if (j < 8) fr[j] = k_frag(kb, j + 8);
+    for (int ks = 0; ks < 8; ++ks) {
+      if (ks >= 4) lds_wait(3, kfr[ks & 3]);   // three refills are younger than the one needed now
+      dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ks & 3], qf[ks], ks == 0 ? negm : dst, 0, 0, 0);
+      kfr[ks & 3] = ks < 4 ? k_frag(kb, ks + 4) : k_frag(kb_next, ks - 4);
       __builtin_amdgcn_sched_barrier(0);
     }
-    const int key_base = kt * kBN;
-    if (key_base + kBN - 1 > L + pos0) {
+  };
+  // causal mask of sub-tile u (keys 32 u ..), applied where the sub-tile reaches past the wave's first row
+  auto mask = [&](f32x16& x, int u) __attribute__((always_inline)) {
+    const int key0 = u * 32;
+    if (key0 + 31 > L + pos0) {
       const int limit = L + pos0 + l32;  // last visible key of this lane's query
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int key = key_base + mt * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
-          if (key > limit) s[mt][e] = -INFINITY;
-        }
+      for (int e = 0; e < 16; ++e) {
+        const int key = key0 + (e >> 2) * 8 + half * 4 + (e & 3);
+        if (key > limit) x[e] = -INFINITY;
+      }
     }
   };
-  // Streaming softmax: the reference maximum only moves when a row maximum exceeds it by more than
-  // 2^kRescaleLog2 (then O and the row sum are rescaled); otherwise exponentials are taken against
-  // the stale reference, which leaves the normalised result unchanged.
-  auto softmax = [&]() __attribute__((always_inline)) {
+  auto row_max = [&](const f32x16& x) __attribute__((always_inline)) {
     float m4[4];   // four independent reduction chains
 #pragma unroll
-    for (int k = 0; k < 4; ++k) m4[k] = fmaxf(s[0][k], s[1][k]);
+    for (int k = 0; k < 4; ++k) m4[k] = fmaxf(x[k], x[k + 4]);
 #pragma unroll
-    for (int e = 4; e < 16; ++e) m4[e & 3] = fmaxf(m4[e & 3], fmaxf(s[0][e], s[1][e]));
+    for (int e = 8; e < 16; ++e) m4[e & 3] = fmaxf(m4[e & 3], x[e]);
     float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
-    mx = fmaxf(mx, swap_halves(mx));
-    if (__any(mx > sm.m_ref + thr)) {
-      const float m_new = fmaxf(sm.m_ref, mx);
-      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((sm.m_ref - m_new) * c);
-      sm.m_ref = m_new;
-      sm.l_run *= alpha;
+    return max_halves(mx);
+  };
+  // Streaming softmax of sub-tile u, held in `cur` relative to the reference.  The reference only moves when a row
+  // maximum exceeds it by more than 2^kRescaleLog2: then O, the row sum, the stored scores of this sub-tile and of the
+  // next one (`nxt`, already computed against the old reference) are shifted.  Otherwise the exponentials are taken
+  // against the stale reference, which leaves the normalised result unchanged.
+  auto softmax = [&](f32x16& cur, f32x16& nxt, int u) __attribute__((always_inline)) {
+    mask(cur, u);
+    const float mx = row_max(cur);
+    if (__builtin_expect(__any(mx > kRescaleLog2), 0)) {
+      const float d = mx > kRescaleLog2 ? mx : 0.f;
+      const float alpha = __builtin_amdgcn_exp2f(-d);
+      m_ref += d;
+      l_run *= alpha;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        negm[e] = -m_ref;
+        cur[e] -= d;
+        nxt[e] -= d;
+      }
 #pragma unroll
       for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[a][e] *= alpha;
     }
-    const float mc = sm.m_ref * c;
-    float sum4[4] = {0.f, 0.f, 0.f, 0.f};   // one partial row sum per 16-key group: independent chains
+    float sum2[2] = {0.f, 0.f};   // two independent chains
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int q2 = 0; q2 < 2; ++q2) {
+      bf16x8 pk;
 #pragma unroll
-      for (int q2 = 0; q2 < 2; ++q2) {
-        bf16x8 pk;
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-          const float e0 = __builtin_amdgcn_exp2f(s[mt][q2 * 8 + e] * c - mc);
-          const float e1 = __builtin_amdgcn_exp2f(s[mt][q2 * 8 + e + 1] * c - mc);
-          sum4[mt * 2 + q2] += e0 + e1;
-          f32x2 pr = {e0, e1};
-          bf16x2 cv = __builtin_convertvector(pr, bf16x2);
-          pk[e] = cv[0];
-          pk[e + 1] = cv[1];
-        }
-        pb[mt * 2 + q2] = pk;
+      for (int e = 0; e < 8; e += 2) {
+        f32x2 pr = {__builtin_amdgcn_exp2f(cur[q2 * 8 + e]), __builtin_amdgcn_exp2f(cur[q2 * 8 + e + 1])};
+        const bf16x2 cv = __builtin_convertvector(pr, bf16x2);
+        // plain adds: the packed dot-product instruction that would add the pair in one step does not run beside
+        // the MFMAs, these do
+        sum2[0] += pr[0];
+        sum2[1] += pr[1];
+        pk[e] = cv[0];
+        pk[e + 1] = cv[1];
       }
-    sm.l_run += (sum4[0] + sum4[1]) + (sum4[2] + sum4[3]);
+      pb[q2] = pk;
+    }
+    l_run += sum2[0] + sum2[1];
   };
-  // O^T += V^T P^T : [128 d][32 queries]
-  auto pv_prefetch = [&](int kt) __attribute__((always_inline)) {
-    const __bf16* vb = Vs + (kt % kVStages) * kTile + v_lane;
+  // O^T += V^T P^T for the sub-tile's 32 keys: [128 d][32 queries].  The ring holds fragments 0..3, requested by
+  // pv_prefetch before the scores and the softmax in between, so waiting for every outstanding read costs nothing.
+  auto pv_prefetch = [&](uint32_t vb) __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) fr[j] = v_frag(vb, j);
+    for (int j = 0; j < 4; ++j) vfr[j] = v_frag(vb, j);
     __builtin_amdgcn_sched_barrier(0);
   };
-  auto pv = [&](int kt) __attribute__((always_inline)) {
-    const __bf16* vb = Vs + (kt % kVStages) * kTile + v_lane;
+  auto pv = [&](uint32_t vb) __attribute__((always_inline)) {
+    lds_wait(0, vfr[0], vfr[1], vfr[2], vfr[3]);
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int g16 = j >> 2, a = j & 3;
-      o[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 7], pb[g16], o[a], 0, 0, 0);
-      if (j < 8) fr[j] = v_frag(vb, j + 8);
+    for (int j = 0; j < 8; ++j) {
+      const int g = j >> 2, a = j & 3;
+      if (j >= 4) lds_wait(2 * (7 - j), vfr[j & 3]);   // each later refill is two reads
+      o[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[j & 3], pb[g], o[a], 0, 0, 0);
+      if (j < 4) vfr[j] = v_frag(vb, j + 4);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
+  auto active = [&](int u) __attribute__((always_inline)) { return u * 32 < wave_key_end; };
 
-  // ---- main loop: the direct loads of tile kt+1 are in flight during the math on tile kt; one barrier per tile
-  load_tile(0);
+  // ---- prologue: tiles K(0), K(1), V(0); scores of sub-tile 0; the reference starts at its row maxima
+  load_k_tile(0, 0);
+  if (n_tiles > 1) load_k_tile(1, 1);
+  load_v_tile(0);
   tile_barrier();
+  const uint32_t k_base = lds_addr(Ks + k_lane), v_base = lds_addr(Vs + v_lane);
+  constexpr uint32_t kStageBytes = kTile * 2, kHalfBytes = 8 * kSeg * 2;
+  if (active(0)) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kfr[j] = k_frag(k_base, j);
+    qk(0, k_base, k_base + kHalfBytes, s[0]);
+    mask(s[0], 0);
+    m_ref = row_max(s[0]);   // finite: key 0 is visible to every query
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      s[0][e] -= m_ref;
+      negm[e] = -m_ref;
+    }
+  }
+
+  // ---- main loop.  Iteration kt starts behind the barrier that published K(kt + 1) and V(kt) and behind which no
+  // wave still reads K(kt - 1) or V(kt - 1): their stages take the direct loads of K(kt + 2) and V(kt + 1), which
+  // are in flight during the whole iteration.  K sits in three LDS stages, V in two; one barrier per tile.
+  int ks_cur = 0;   // stage of K(kt)
   for (int kt = 0; kt < n_tiles; ++kt) {
-    if (((kt + 1) & 15) == 0) { ak_cur = ak_nxt; av_cur = av_nxt; }
-    // the other stage was last read one iteration ago, before the barrier every wave has passed
-    if (kt + 1 < n_tiles) load_tile(kt + 1);
-    if (((kt + 2) & 15) == 0) fetch_window((kt + 2) >> 4, ak_nxt, av_nxt);
-    if (kt * kBN < wave_key_end) {
-      qk(kt);
-      pv_prefetch(kt);
-      softmax();
-      pv(kt);
+    const int ks_nxt = ks_cur == 2 ? 0 : ks_cur + 1;    // stage of K(kt + 1)
+    const int ks_ld = ks_nxt == 2 ? 0 : ks_nxt + 1;     // stage of K(kt + 2) = the one K(kt - 1) leaves
+    if (((kt + 1) >> 4) != win) {   // V enters the next window: move on, fetch the one after it
+      ++win;
+      ak_cur = ak_nxt;
+      av_cur = av_nxt;
+      fetch_window(win + 1, ak_nxt, av_nxt);
+    }
+    if (kt + 2 < n_tiles) load_k_tile(kt + 2, ks_ld);
+    if (kt + 1 < n_tiles) load_v_tile(kt + 1);
+    const uint32_t kb0 = k_base + ks_cur * kStageBytes;   // K(kt)
+    const uint32_t kb1 = k_base + ks_nxt * kStageBytes;   // K(kt + 1)
+    const uint32_t vb = v_base + (kt & 1) * kStageBytes;  // V(kt)
+    const int u = 2 * kt;
+    // first half: scores of (kt, keys 32..63), softmax and output update of (kt, keys 0..31)
+    if (active(u)) pv_prefetch(vb);
+    if (active(u + 1)) qk(8, kb0 + kHalfBytes, kb1, s[1]);
+    if (active(u)) {
+      softmax(s[0], s[1], u);
+      pv(vb);
+    }
+    // second half: scores of (kt + 1, keys 0..31), softmax and output update of (kt, keys 32..63)
+    if (active(u + 1)) pv_prefetch(vb + kHalfBytes);
+    if (active(u + 2)) qk(8, kb1, kb1 + kHalfBytes, s[0]);
+    if (active(u + 1)) {
+      softmax(s[1], s[0], u + 1);
+      pv(vb + kHalfBytes);
     }
     tile_barrier();
+    ks_cur = ks_nxt;
   }
 
   // ---- normalise and store.  A lane holds query l32 with d = 32 a + 8 (e/4) + 4 half + e%4, i.e. sixteen 8-byte
   // pieces of one output row.  They go through the wave's staging tile and leave as whole 256-byte rows.
   if (pos0 >= row1) return;
   {
-    const float lsum = sm.l_run + swap_halves(sm.l_run);
+    const float lsum = l_run + swap_halves(l_run);
     const float inv = 1.0f / lsum;
     {
       __bf16* row = stage + l32 * kD;
