@@ -11,11 +11,14 @@
 // softmax on the vector ALU.  A workgroup of eight wavefronts shares every K/V tile through
 // LDS; each wavefront owns 32 query rows of one head (the query heads of one kv head share a
 // workgroup, so a K/V tile is fetched once for the group).  K/V rows travel global -> LDS with
-// direct-to-LDS loads (no stop in registers, no LDS store instructions).  The products are
-// formed transposed (S^T = K Q^T, O^T = V^T P^T) so that a query is a lane-column of the MFMA
-// accumulator: row max / row sum are register reductions plus one cross-half exchange, and
-// the P^T accumulator registers are already in the B-operand layout of the second product;
-// V^T fragments come from the LDS transpose load.
+// direct-to-LDS loads (no stop in registers, no LDS store instructions), three stages each.
+// The products are formed transposed (S^T = K Q^T, O^T = V^T P^T) so that a query is a
+// lane-column of the MFMA accumulator: row sums are register reductions, and the P^T
+// accumulator registers are already in the B-operand layout of the second product; V^T
+// fragments come from the LDS transpose load.  The inner loop is a three-stage software
+// pipeline over 32-key sub-tiles: the scores of sub-tile h + 1, the softmax of sub-tile h and
+// the output update with sub-tile h - 1 share a half-step, in which nothing depends on
+// anything else, so MFMAs and vector instructions alternate in the instruction stream.
 // fp32 path: one wavefront per output row, plain fp32 arithmetic (correctness configuration).
 #include <atomic>
 
@@ -35,9 +38,10 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr int kD = 128;          // head dim of the bf16 kernel
 constexpr int kBN = 64;          // keys per LDS tile
-constexpr int kKStages = 3;      // LDS stages of K (scores run one sub-tile ahead of the output update)
-constexpr int kVStages = 2;      // LDS stages of V
-constexpr float kRescaleLog2 = 8.f;  // move the softmax reference when a row maximum exceeds it by 2^8
+constexpr int kKStages = 3;      // LDS stages of K: tiles kt, kt + 1 in use, kt + 2 arriving
+constexpr int kVStages = 3;      // LDS stages of V: tiles kt - 1, kt in use, kt + 1 arriving
+constexpr int kStageRows = 16;   // rows of a wave's Q / O staging tile
+constexpr float kSumLimit = 4096.f;   // move the softmax reference when a lane's sum of 16 exponentials exceeds this
 constexpr int kRowsPerWave = 32; // query rows per wavefront
 constexpr int kWaves = 8;        // two per SIMD: one wave's softmax overlaps the other's MFMAs
 constexpr int kThreads = kWaves * 64;
@@ -168,12 +172,13 @@ __device__ __forceinline__ void lds_wait(int n, bf16x8& a, bf16x8& b, bf16x8& c,
 
 __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   __shared__ __attribute__((aligned(16))) __bf16 smem[kKStages * kTile + kVStages * kTile +
-                                                      kWaves * kRowsPerWave * kD];
+                                                      kWaves * kStageRows * kD];
   __bf16* const Ks = smem;
   __bf16* const Vs = smem + kKStages * kTile;
-  // [kWaves][32 rows][16 chunks of 8 bf16]: each wave's own staging tile for its Q rows on the way in and its O rows
-  // on the way out, 16-byte chunks XOR-swizzled by row so that row-wise and fragment-wise accesses are conflict free
-  __bf16* const stage = Vs + kVStages * kTile + (threadIdx.x >> 6) * (kRowsPerWave * kD);
+  // [kWaves][16 rows][16 chunks of 8 bf16]: each wave's own staging tile for its Q rows on the way in and its O rows
+  // on the way out (16 rows at a time), 16-byte chunks XOR-swizzled by row so that row-wise and fragment-wise
+  // accesses are conflict free
+  __bf16* const stage = Vs + kVStages * kTile + (threadIdx.x >> 6) * (kStageRows * kD);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -233,19 +238,25 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
       qv[i] = *(const u32x4*)((const __bf16*)p.q + ((size_t)(qbase + row) * p.Hq + head) * kD + c16 * 8);
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int rr = (lane >> 4) + 4 * i;
-      u32x4 w;
+    for (int pass = 0; pass < 2; ++pass) {   // the staging tile takes 16 rows at a time
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const uint32_t x = qv[i][k];
-        f32x2 pr = {__builtin_bit_cast(float, x << 16) * c, __builtin_bit_cast(float, x & 0xffff0000u) * c};
-        w[k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+      for (int i = 0; i < 4; ++i) {
+        const int rr = (lane >> 4) + 4 * i;    // row within the pass
+        u32x4 w;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const uint32_t x = qv[4 * pass + i][k];
+          f32x2 pr = {__builtin_bit_cast(float, x << 16) * c, __builtin_bit_cast(float, x & 0xffff0000u) * c};
+          w[k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+        }
+        *(u32x4*)(stage + rr * kD + ((c16 ^ rr) << 3)) = w;
       }
-      *(u32x4*)(stage + rr * kD + ((c16 ^ (rr & 15)) << 3)) = w;
-    }
+      if ((l32 >> 4) == pass) {
+        const int rr = l32 & 15;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8*)(stage + l32 * kD + (((2 * ks + half) ^ (l32 & 15)) << 3));
+        for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8*)(stage + rr * kD + (((2 * ks + half) ^ rr) << 3));
+      }
+    }
   }
 
   f32x16 o[4];   // O^T accumulators: d = 32 a + 8(e/4) + 4 half + e%4, query = l32
@@ -318,8 +329,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   auto load_k_tile = [&](int t, int stage_idx) __attribute__((always_inline)) {
     load_half_tile((t >> 4) == win ? ak_cur : ak_nxt, t, Ks + stage_idx * kTile);
   };
-  auto load_v_tile = [&](int t) __attribute__((always_inline)) {
-    load_half_tile((t >> 4) == win ? av_cur : av_nxt, t, Vs + (t & 1) * kTile);
+  auto load_v_tile = [&](int t, int stage_idx) __attribute__((always_inline)) {
+    load_half_tile((t >> 4) == win ? av_cur : av_nxt, t, Vs + stage_idx * kTile);
   };
   // a wave's direct loads are in LDS once its vector-memory counter has drained; the barrier then publishes them
   auto tile_barrier = [&]() __attribute__((always_inline)) {
@@ -328,19 +339,22 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   };
 
   // ---- the steps of the pipeline ----
-  // Work advances in 32-key sub-tiles (half an LDS tile).  The scores of sub-tile u + 1 are put on the matrix core
-  // BEFORE the softmax of sub-tile u is computed on the vector ALU, and the output update with sub-tile u follows it:
-  // neighbouring matrix and vector blocks of the instruction stream never depend on each other, so they run
-  // side by side.  Two score accumulators alternate.
-  f32x16 s[2];      // S^T of two consecutive sub-tiles: [32 keys][32 queries], already minus the softmax reference
-  f32x16 negm;      // minus the reference, in every element: C operand of the first score MFMA of a sub-tile
-  bf16x8 pb[2];     // P^T as B operands, one per 16-key group of the sub-tile
+  // Work advances in 32-key sub-tiles (half an LDS tile), three of them in flight: half-step h puts the scores of
+  // sub-tile h + 1 and the output update with sub-tile h - 1 on the matrix core and computes the softmax of sub-tile
+  // h on the vector ALU.  Nothing inside a half-step depends on anything else inside it, so its 16 MFMAs alternate
+  // (score, output, score, ...) with two or three vector instructions behind each: the vector work runs beside the
+  // MFMAs instead of between them.  Two score accumulators and two P^T buffers alternate.
+  f32x16 s[2];      // S^T of two consecutive sub-tiles: [32 keys][32 queries], in log2 units (Q carries the scale)
+  bf16x8 pb[2][2];  // P^T as B operands: [sub-tile parity][16-key group]
   bf16x8 kfr[4];    // K fragment ring: runs four fragments ahead, across sub-tiles
-  bf16x8 vfr[4];    // V^T fragment ring
-  float m_ref = 0.f;   // reference the stored scores are relative to (log2 units), per query
+  bf16x8 vfr[4];    // V^T fragment ring, likewise
+  float m_ref = 0.f;   // reference the exponentials are taken against (log2 units), per query
   float l_run = 0.f;   // running row sum over this lane-half's keys
 #pragma unroll
-  for (int e = 0; e < 16; ++e) negm[e] = s[0][e] = s[1][e] = 0.f;
+  for (int e = 0; e < 16; ++e) s[0][e] = s[1][e] = 0.f;
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) pb[0][0][e] = pb[0][1][e] = pb[1][0][e] = pb[1][1][e] = (__bf16)0.f;
   // K fragment (ks, mt): lane (l32, half) wants key l32 + 32 mt, chunk 2 ks + half.  In bf16 elements:
   //   segment (l32 / 4 + 8 mt) * kSeg + key-in-segment (l32 % 4) * 32 + (ks / 2) * 128 + (2 (ks % 2) + half) * 8
   const int k_lane = (l32 >> 2) * kSeg + (l32 & 3) * 32 + half * 8;
@@ -360,19 +374,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
     const s16x4 lo = lds_read_tr16_b64(vb, off);
     const s16x4 hi = lds_read_tr16_b64(vb, off + 2 * kSeg * 2);
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-  };
-  // Scores of one sub-tile: dst = K Q^T - reference.  The ring holds fragments 0..3 of this sub-tile, requested during
-  // the previous call; it is refilled with fragments 4..7 and then with fragments 0..3 of the sub-tile that follows
-  // (kb_next).  younger: LDS reads issued since that previous call (the V^T prefetch of this step).
-  auto qk = [&](int younger, uint32_t kb, uint32_t kb_next, f32x16& dst) __attribute__((always_inline)) {
-    lds_wait(younger, kfr[0], kfr[1], kfr[2], kfr[3]);
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      if (ks >= 4) lds_wait(3, kfr[ks & 3]);   // three refills are younger than the one needed now
-      dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ks & 3], qf[ks], ks == 0 ? negm : dst, 0, 0, 0);
-      kfr[ks & 3] = ks < 4 ? k_frag(kb, ks + 4) : k_frag(kb_next, ks - 4);
-      __builtin_amdgcn_sched_barrier(0);
-    }
   };
   // causal mask of sub-tile u (keys 32 u ..), applied where the sub-tile reaches past the wave's first row
   auto mask = [&](f32x16& x, int u) __attribute__((always_inline)) {
@@ -395,154 +396,212 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
     float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
     return max_halves(mx);
   };
-  // Streaming softmax of sub-tile u, held in `cur` relative to the reference.  The reference only moves when a row
-  // maximum exceeds it by more than 2^kRescaleLog2: then O, the row sum, the stored scores of this sub-tile and of the
-  // next one (`nxt`, already computed against the old reference) are shifted.  Otherwise the exponentials are taken
-  // against the stale reference, which leaves the normalised result unchanged.
-  auto softmax = [&](f32x16& cur, f32x16& nxt, int u) __attribute__((always_inline)) {
-    mask(cur, u);
+  // exponentials of one pair of scores -> packed bf16, plain fp32 adds for the row sum (the packed dot-product
+  // instruction that would add the pair in one step does not run beside the MFMAs, the adds do)
+  float ssum[2];
+  bf16x8 pk;
+  auto exp_pair = [&](const f32x16& cur, int i, bf16x8 (&p_make)[2], float& e0, float& e1, int part) __attribute__((always_inline)) {
+    if (part == 0) {
+      e0 = __builtin_amdgcn_exp2f(cur[2 * i] - m_ref);
+      e1 = __builtin_amdgcn_exp2f(cur[2 * i + 1] - m_ref);
+    } else {
+      f32x2 pr = {e0, e1};
+      const bf16x2 cv = __builtin_convertvector(pr, bf16x2);
+      ssum[0] += e0;
+      ssum[1] += e1;
+      pk[2 * (i & 3)] = cv[0];
+      pk[2 * (i & 3) + 1] = cv[1];
+      if ((i & 3) == 3) p_make[i >> 2] = pk;
+    }
+  };
+  // The softmax keeps a reference per query; exponentials are taken against it as it stands, which leaves the
+  // normalised result unchanged.  Only when a lane's sum of exponentials over a sub-tile passes kSumLimit (an element
+  // at least kSumLimit / 16 above the reference; infinities and NaNs trip it too) is the reference moved to that
+  // sub-tile's row maximum: O and the row sum are rescaled and this sub-tile's exponentials are taken again.  This
+  // happens between half-steps, after the output update that still belongs to the old reference has been issued.
+  auto move_reference = [&](const f32x16& cur, bf16x8 (&p_make)[2]) __attribute__((always_inline)) {
     const float mx = row_max(cur);
-    if (__builtin_expect(__any(mx > kRescaleLog2), 0)) {
-      const float d = mx > kRescaleLog2 ? mx : 0.f;
-      const float alpha = __builtin_amdgcn_exp2f(-d);
-      m_ref += d;
-      l_run *= alpha;
+    const bool trip = !(max_halves(ssum[0] + ssum[1]) <= kSumLimit);
+    const float m_new = trip ? mx : m_ref;
+    const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+    m_ref = m_new;
+    l_run *= alpha;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        negm[e] = -m_ref;
-        cur[e] -= d;
-        nxt[e] -= d;
-      }
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-      for (int a = 0; a < 4; ++a)
+      for (int e = 0; e < 16; ++e) o[a][e] *= alpha;
+    ssum[0] = ssum[1] = 0.f;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) o[a][e] *= alpha;
-    }
-    float sum2[2] = {0.f, 0.f};   // two independent chains
-#pragma unroll
-    for (int q2 = 0; q2 < 2; ++q2) {
-      bf16x8 pk;
-#pragma unroll
-      for (int e = 0; e < 8; e += 2) {
-        f32x2 pr = {__builtin_amdgcn_exp2f(cur[q2 * 8 + e]), __builtin_amdgcn_exp2f(cur[q2 * 8 + e + 1])};
-        const bf16x2 cv = __builtin_convertvector(pr, bf16x2);
-        // plain adds: the packed dot-product instruction that would add the pair in one step does not run beside
-        // the MFMAs, these do
-        sum2[0] += pr[0];
-        sum2[1] += pr[1];
-        pk[e] = cv[0];
-        pk[e + 1] = cv[1];
-      }
-      pb[q2] = pk;
-    }
-    l_run += sum2[0] + sum2[1];
-  };
-  // O^T += V^T P^T for the sub-tile's 32 keys: [128 d][32 queries].  The ring holds fragments 0..3, requested by
-  // pv_prefetch before the scores and the softmax in between, so waiting for every outstanding read costs nothing.
-  auto pv_prefetch = [&](uint32_t vb) __attribute__((always_inline)) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) vfr[j] = v_frag(vb, j);
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  auto pv = [&](uint32_t vb) __attribute__((always_inline)) {
-    lds_wait(0, vfr[0], vfr[1], vfr[2], vfr[3]);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int g = j >> 2, a = j & 3;
-      if (j >= 4) lds_wait(2 * (7 - j), vfr[j & 3]);   // each later refill is two reads
-      o[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[j & 3], pb[g], o[a], 0, 0, 0);
-      if (j < 4) vfr[j] = v_frag(vb, j + 4);
-      __builtin_amdgcn_sched_barrier(0);
+    for (int i = 0; i < 8; ++i) {
+      float e0, e1;
+      exp_pair(cur, i, p_make, e0, e1, 0);
+      exp_pair(cur, i, p_make, e0, e1, 1);
     }
   };
   auto active = [&](int u) __attribute__((always_inline)) { return u * 32 < wave_key_end; };
+  // One half-step.  kb / kb_next: K of sub-tiles h + 1 and h + 2; vb / vb_next: V of sub-tiles h - 1 and h.
+  // The rings hold fragments 0..3 of sub-tile h + 1 (K) and of sub-tile h - 1 (V^T) on entry and are refilled behind
+  // each MFMA with fragments 4..7 and then with fragments 0..3 of the following sub-tile.
+  // Fast form (every stage at work, no masked key in sub-tile h): the 16 MFMAs alternate and carry the softmax between
+  // them; a fragment is waited for four pair-steps after its request, with eleven (K) or ten (V^T) younger reads.
+  auto half_step_fast = [&](uint32_t kb, uint32_t kb_next, uint32_t vb, uint32_t vb_next, f32x16& dst, f32x16& cur,
+                            bf16x8 (&p_use)[2], bf16x8 (&p_make)[2]) __attribute__((always_inline)) {
+    ssum[0] = ssum[1] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float e0, e1;
+      lds_wait(11, kfr[i & 3]);
+      dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[i & 3], qf[i], i == 0 ? zero16 : dst, 0, 0, 0);
+      kfr[i & 3] = i < 4 ? k_frag(kb, i + 4) : k_frag(kb_next, i - 4);
+      exp_pair(cur, i, p_make, e0, e1, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      lds_wait(10, vfr[i & 3]);
+      o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[i & 3], p_use[i >> 2], o[i & 3], 0, 0, 0);
+      vfr[i & 3] = i < 4 ? v_frag(vb, i + 4) : v_frag(vb_next, i - 4);
+      exp_pair(cur, i, p_make, e0, e1, 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (__builtin_expect(__any(!(ssum[0] + ssum[1] <= kSumLimit)), 0)) move_reference(cur, p_make);
+    l_run += ssum[0] + ssum[1];
+  };
+  // General form (first and last iterations of a wave): each stage is tested, runs as a block of its own, and waits
+  // for every outstanding read.
+  auto half_step_slow = [&](int h, uint32_t kb, uint32_t kb_next, uint32_t vb, uint32_t vb_next, f32x16& dst,
+                            f32x16& cur, bf16x8 (&p_use)[2], bf16x8 (&p_make)[2]) __attribute__((always_inline)) {
+    if (active(h + 1)) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        lds_wait(0, kfr[i & 3]);
+        dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[i & 3], qf[i], i == 0 ? zero16 : dst, 0, 0, 0);
+        kfr[i & 3] = i < 4 ? k_frag(kb, i + 4) : k_frag(kb_next, i - 4);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    if (h > 0 && active(h - 1)) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        lds_wait(0, vfr[i & 3]);
+        o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[i & 3], p_use[i >> 2], o[i & 3], 0, 0, 0);
+        vfr[i & 3] = i < 4 ? v_frag(vb, i + 4) : v_frag(vb_next, i - 4);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) vfr[j] = v_frag(vb_next, j);   // the ring enters the next half-step as it expects
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (active(h)) {
+      mask(cur, h);
+      ssum[0] = ssum[1] = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float e0, e1;
+        exp_pair(cur, i, p_make, e0, e1, 0);
+        exp_pair(cur, i, p_make, e0, e1, 1);
+      }
+      if (__builtin_expect(__any(!(ssum[0] + ssum[1] <= kSumLimit)), 0)) move_reference(cur, p_make);
+      l_run += ssum[0] + ssum[1];
+    }
+    // whatever follows finds every fragment of the rings in place
+    lds_wait(0, kfr[0], kfr[1], kfr[2], kfr[3]);
+    lds_wait(0, vfr[0], vfr[1], vfr[2], vfr[3]);
+  };
 
   // ---- prologue: tiles K(0), K(1), V(0); scores of sub-tile 0; the reference starts at its row maxima
   load_k_tile(0, 0);
   if (n_tiles > 1) load_k_tile(1, 1);
-  load_v_tile(0);
+  load_v_tile(0, 0);
   tile_barrier();
   const uint32_t k_base = lds_addr(Ks + k_lane), v_base = lds_addr(Vs + v_lane);
   constexpr uint32_t kStageBytes = kTile * 2, kHalfBytes = 8 * kSeg * 2;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    kfr[j] = k_frag(k_base, j);
+    vfr[j] = kfr[j];   // defined; the V^T ring fills itself during half-step 0
+  }
   if (active(0)) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) kfr[j] = k_frag(k_base, j);
-    qk(0, k_base, k_base + kHalfBytes, s[0]);
+    for (int ks = 0; ks < 8; ++ks) {
+      lds_wait(0, kfr[ks & 3]);
+      s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ks & 3], qf[ks], ks == 0 ? zero16 : s[0], 0, 0, 0);
+      kfr[ks & 3] = ks < 4 ? k_frag(k_base, ks + 4) : k_frag(k_base + kHalfBytes, ks - 4);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     mask(s[0], 0);
     m_ref = row_max(s[0]);   // finite: key 0 is visible to every query
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      s[0][e] -= m_ref;
-      negm[e] = -m_ref;
-    }
   }
 
-  // ---- main loop.  Iteration kt starts behind the barrier that published K(kt + 1) and V(kt) and behind which no
-  // wave still reads K(kt - 1) or V(kt - 1): their stages take the direct loads of K(kt + 2) and V(kt + 1), which
-  // are in flight during the whole iteration.  K sits in three LDS stages, V in two; one barrier per tile.
-  int ks_cur = 0;   // stage of K(kt)
-  for (int kt = 0; kt < n_tiles; ++kt) {
-    const int ks_nxt = ks_cur == 2 ? 0 : ks_cur + 1;    // stage of K(kt + 1)
-    const int ks_ld = ks_nxt == 2 ? 0 : ks_nxt + 1;     // stage of K(kt + 2) = the one K(kt - 1) leaves
+  // ---- main loop.  Iteration kt (two half-steps) reads K(kt), K(kt + 1), V(kt - 1), V(kt).  It starts behind the
+  // barrier that published K(kt + 1) and V(kt) and behind which no wave still reads K(kt - 1) or V(kt - 2): their
+  // stages take the direct loads of K(kt + 2) and V(kt + 1), in flight during the whole iteration.  One barrier per
+  // tile; one more iteration than tiles, for the output update with the last sub-tile.
+  // Iterations [1, kt_fast) of this wave have all three stages at work, no masked key and no ragged tile to load.
+  const int kt_fast = min(min((L + pos0 - 63) / 64 + 1, (wave_key_end - 1) / 64), n_tiles - 3);
+  int st0 = 0;   // stage of K(kt) and V(kt); tile t sits in stage t % 3
+  auto iteration = [&]<bool kFast>(int kt) __attribute__((always_inline)) {
+    const int st1 = st0 == 2 ? 0 : st0 + 1;    // stage of tile kt + 1
+    const int st2 = st1 == 2 ? 0 : st1 + 1;    // stage of tiles kt + 2 and kt - 1
     if (((kt + 1) >> 4) != win) {   // V enters the next window: move on, fetch the one after it
       ++win;
       ak_cur = ak_nxt;
       av_cur = av_nxt;
       fetch_window(win + 1, ak_nxt, av_nxt);
     }
-    if (kt + 2 < n_tiles) load_k_tile(kt + 2, ks_ld);
-    if (kt + 1 < n_tiles) load_v_tile(kt + 1);
-    const uint32_t kb0 = k_base + ks_cur * kStageBytes;   // K(kt)
-    const uint32_t kb1 = k_base + ks_nxt * kStageBytes;   // K(kt + 1)
-    const uint32_t vb = v_base + (kt & 1) * kStageBytes;  // V(kt)
-    const int u = 2 * kt;
-    // first half: scores of (kt, keys 32..63), softmax and output update of (kt, keys 0..31)
-    if (active(u)) pv_prefetch(vb);
-    if (active(u + 1)) qk(8, kb0 + kHalfBytes, kb1, s[1]);
-    if (active(u)) {
-      softmax(s[0], s[1], u);
-      pv(vb);
-    }
-    // second half: scores of (kt + 1, keys 0..31), softmax and output update of (kt, keys 32..63)
-    if (active(u + 1)) pv_prefetch(vb + kHalfBytes);
-    if (active(u + 2)) qk(8, kb1, kb1 + kHalfBytes, s[0]);
-    if (active(u + 1)) {
-      softmax(s[1], s[0], u + 1);
-      pv(vb + kHalfBytes);
+    if (kFast || kt + 2 < n_tiles) load_k_tile(kt + 2, st2);
+    if (kFast || kt + 1 < n_tiles) load_v_tile(kt + 1, st1);
+    const uint32_t kb0 = k_base + st0 * kStageBytes;   // K(kt)
+    const uint32_t kb1 = k_base + st1 * kStageBytes;   // K(kt + 1)
+    const uint32_t vbp = v_base + st2 * kStageBytes;   // V(kt - 1)
+    const uint32_t vb0 = v_base + st0 * kStageBytes;   // V(kt)
+    if (kFast) {
+      half_step_fast(kb0 + kHalfBytes, kb1, vbp + kHalfBytes, vb0, s[1], s[0], pb[1], pb[0]);
+      half_step_fast(kb1, kb1 + kHalfBytes, vb0, vb0 + kHalfBytes, s[0], s[1], pb[0], pb[1]);
+    } else {
+      half_step_slow(2 * kt, kb0 + kHalfBytes, kb1, vbp + kHalfBytes, vb0, s[1], s[0], pb[1], pb[0]);
+      half_step_slow(2 * kt + 1, kb1, kb1 + kHalfBytes, vb0, vb0 + kHalfBytes, s[0], s[1], pb[0], pb[1]);
     }
     tile_barrier();
-    ks_cur = ks_nxt;
-  }
+    st0 = st1;
+  };
+  int kt = 0;
+  iteration.template operator()<false>(kt++);
+  for (; kt < kt_fast; ++kt) iteration.template operator()<true>(kt);
+  for (; kt <= n_tiles; ++kt) iteration.template operator()<false>(kt);
 
   // ---- normalise and store.  A lane holds query l32 with d = 32 a + 8 (e/4) + 4 half + e%4, i.e. sixteen 8-byte
-  // pieces of one output row.  They go through the wave's staging tile and leave as whole 256-byte rows.
+  // pieces of one output row.  They go through the wave's staging tile, 16 rows at a time, and leave as whole
+  // 256-byte rows.
   if (pos0 >= row1) return;
   {
     const float lsum = l_run + swap_halves(l_run);
     const float inv = 1.0f / lsum;
-    {
-      __bf16* row = stage + l32 * kD;
-#pragma unroll
-      for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          f32x2 x0 = {o[a][i4 * 4 + 0] * inv, o[a][i4 * 4 + 1] * inv};
-          f32x2 x1 = {o[a][i4 * 4 + 2] * inv, o[a][i4 * 4 + 3] * inv};
-          bf16x2 y0 = __builtin_convertvector(x0, bf16x2);
-          bf16x2 y1 = __builtin_convertvector(x1, bf16x2);
-          u32x2 wv = {__builtin_bit_cast(uint32_t, y0), __builtin_bit_cast(uint32_t, y1)};
-          const int chunk = a * 4 + i4;   // d = 8 chunk + 4 half .. + 3
-          *(u32x2*)(row + (((chunk ^ (l32 & 15)) << 3) + 4 * half)) = wv;
-        }
-    }
-    // same wave wrote and reads: the LDS operations of one wave complete in order
     const int c16 = lane & 15;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int rr = (lane >> 4) + 4 * i;   // row of this wave's tile
-      const int pos = pos0 + rr;
-      const u32x4 v = *(const u32x4*)(stage + rr * kD + ((c16 ^ (rr & 15)) << 3));
-      if (pos < row1) *(u32x4*)((__bf16*)p.out + ((size_t)(qbase + pos) * p.Hq + head) * kD + c16 * 8) = v;
+    for (int pass = 0; pass < 2; ++pass) {
+      if ((l32 >> 4) == pass) {
+        const int rr = l32 & 15;
+        __bf16* row = stage + rr * kD;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            f32x2 x0 = {o[a][i4 * 4 + 0] * inv, o[a][i4 * 4 + 1] * inv};
+            f32x2 x1 = {o[a][i4 * 4 + 2] * inv, o[a][i4 * 4 + 3] * inv};
+            bf16x2 y0 = __builtin_convertvector(x0, bf16x2);
+            bf16x2 y1 = __builtin_convertvector(x1, bf16x2);
+            u32x2 wv = {__builtin_bit_cast(uint32_t, y0), __builtin_bit_cast(uint32_t, y1)};
+            const int chunk = a * 4 + i4;   // d = 8 chunk + 4 half .. + 3
+            *(u32x2*)(row + (((chunk ^ rr) << 3) + 4 * half)) = wv;
+          }
+      }
+      // same wave wrote and reads: the LDS operations of one wave complete in order
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int rr = (lane >> 4) + 4 * i;   // row within the pass
+        const int pos = pos0 + 16 * pass + rr;
+        const u32x4 v = *(const u32x4*)(stage + rr * kD + ((c16 ^ rr) << 3));
+        if (pos < row1) *(u32x4*)((__bf16*)p.out + ((size_t)(qbase + pos) * p.Hq + head) * kD + c16 * 8) = v;
+      }
     }
   }
 }
