@@ -255,6 +255,13 @@ int skv_scatter_kv(const skv_attn_desc* desc, int32_t n_req, const void* d_knew,
                    const int32_t* d_q_off, const int32_t* d_new_pages, int32_t max_new_blocks, void* d_kpool,
                    void* d_vpool, int32_t n_pages, void* stream);
 
+/* Plain device-to-device streaming copy of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned, the
+ * ranges must not overlap), with the same vector width and access shape as the page copies of skv_gather_kv and
+ * skv_scatter_kv but no page table.  It is the copy of known size that HBM traffic counters are scaled by, and
+ * its rate is the box's own copy ceiling that the gather (Section 4.3.2) is compared with.
+ * Errors: SKV_EINVAL for null or misaligned pointers or a size that is not a multiple of 16. */
+int skv_stream_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
+
 /* Bytes of device workspace skv_prefill_attn needs for n_req requests and at most
  * total_q_rows uncached tokens in the batch (the work list of the bf16 kernel and one page of zeros that
  * stands in for key groups without data); the call overwrites it. */

@@ -20,7 +20,7 @@ SKV_OK, SKV_EINVAL, SKV_ENOMEM, SKV_ERANGE, SKV_EHIP = 0, -1, -2, -3, -4
 EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_size_for_capacity", "skv_tree_build", "skv_tree_insert", "skv_set_epoch", "skv_block_epochs_read", "skv_evict",
            "skv_tree_info", "skv_tree_destroy", "skv_match", "skv_counters_read",
            "skv_counters_reset", "skv_window_roll", "skv_promote", "skv_block_state_read", "skv_suffix_offsets", "skv_gather_kv",
-           "skv_scatter_kv", "skv_decode_attn_workspace_size", "skv_decode_attn",
+           "skv_scatter_kv", "skv_stream_copy", "skv_decode_attn_workspace_size", "skv_decode_attn",
            "skv_prefill_attn_workspace_size", "skv_prefill_attn", "skv_prefill_attn_static"]
 
 
@@ -88,6 +88,7 @@ def lib():
                                        i32, vp, vp, C.c_size_t, vp]
         l.skv_prefill_attn_static.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp,
                                               i32, vp, vp]
+        l.skv_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
         _lib = l
     return _lib
 
@@ -251,6 +252,12 @@ def skv_scatter_kv(desc: AttnDesc, knew, vnew, q_off, new_pages, kpool, vpool, s
     _check(lib().skv_scatter_kv(C.byref(desc), n_req, _dptr(knew), _dptr(vnew), _dptr(q_off), _dptr(new_pages),
                                 new_pages.shape[1], _dptr(kpool), _dptr(vpool), kpool.shape[0], _stream(stream)),
            "skv_scatter_kv")
+
+
+def skv_stream_copy(dst, src, stream=None):
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() >= nbytes
+    _check(lib().skv_stream_copy(_dptr(dst), _dptr(src), nbytes, _stream(stream)), "skv_stream_copy")
 
 
 def skv_block_state_read(tree: Tree, private, hit_pre, u_pre, stream=None):

@@ -121,7 +121,38 @@ __global__ __launch_bounds__(kThreads) void scatter_pages_kernel(
   }
 }
 
+// Plain streaming copy, same vector width and loads-before-stores shape as the page copies above.
+__global__ __launch_bounds__(kThreads) void stream_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                               int64_t n_vec) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads * kUnroll;
+  for (int64_t base = (int64_t)blockIdx.x * kThreads * kUnroll; base < n_vec; base += stride) {
+    u32x4 a[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int64_t i = base + (int64_t)u * kThreads + threadIdx.x;
+      if (i < n_vec) a[u] = __builtin_nontemporal_load(src + i);
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int64_t i = base + (int64_t)u * kThreads + threadIdx.x;
+      if (i < n_vec) __builtin_nontemporal_store(a[u], dst + i);
+    }
+  }
+}
+
 }  // namespace
+
+extern "C" int skv_stream_copy(void* d_dst, const void* d_src, size_t bytes, void* stream) {
+  if (bytes == 0) return SKV_OK;
+  if (!d_dst || !d_src || (bytes & 15) || (((uintptr_t)d_dst | (uintptr_t)d_src) & 15)) return SKV_EINVAL;
+  const int64_t n_vec = (int64_t)(bytes / 16);
+  const int64_t per_wg = (int64_t)kThreads * kUnroll;
+  const int64_t want = (n_vec + per_wg - 1) / per_wg;
+  stream_copy_kernel<<<(int)(want < 256 * 16 ? want : 256 * 16), kThreads, 0, (hipStream_t)stream>>>(
+      (const u32x4*)d_src, (u32x4*)d_dst, n_vec);
+  SKV_HIP(hipGetLastError());
+  return SKV_OK;
+}
 
 extern "C" int skv_scatter_kv(const skv_attn_desc* desc, int32_t n_req, const void* d_knew, const void* d_vnew,
                               const int32_t* d_q_off, const int32_t* d_new_pages, int32_t max_new_blocks,

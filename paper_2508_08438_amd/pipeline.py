@@ -9,9 +9,25 @@ from . import binding as skv
 from .inputs import BLOCK, Workload
 
 
+def _tiled_from_host(chunk: torch.Tensor, n_rows: int, device) -> torch.Tensor:
+    """[n_rows, ...] device tensor filled with repetitions of a host chunk: host-to-device copies only."""
+    out = torch.empty((n_rows,) + tuple(chunk.shape[1:]), dtype=chunk.dtype, device=device)
+    step = chunk.shape[0]
+    for lo in range(0, n_rows, step):
+        hi = min(n_rows, lo + step)
+        out[lo:hi].copy_(chunk[: hi - lo])
+    return out
+
+
 class Session:
-    def __init__(self, w: Workload, device="cuda:0", with_kv=True, gather=True):
-        self.w, self.device, self.do_gather = w, torch.device(device), gather
+    """host_fill=True builds every device buffer from host memory with plain copies, so that no torch device
+    kernel runs in the process (for hardware-counter runs, which must see the library's kernels only).  Pools and
+    Q/K/V then hold repetitions of one host-generated chunk: same shapes and access pattern, other values.
+    kpool / vpool: pools of another session of the same configuration and seed, shared instead of filled again."""
+
+    def __init__(self, w: Workload, device="cuda:0", with_kv=True, gather=True, host_fill=False, kpool=None,
+                 vpool=None):
+        self.w, self.device, self.do_gather, self.host_fill = w, torch.device(device), gather, host_fill
         dev = self.device
         a = w.attn
         self.desc = skv.attn_desc(a.n_q_heads, a.n_kv_heads, a.head_dim, a.dtype, a.scale)
@@ -22,17 +38,22 @@ class Session:
         self.req_tenant = torch.from_numpy(w.req_tenant).to(dev)
         R = w.n_req
         self.max_blocks = max(w.max_blocks, 1)
-        self.matched_len = torch.zeros(R, dtype=torch.int32, device=dev)
-        self.page_table = torch.full((R, self.max_blocks), -1, dtype=torch.int32, device=dev)
-        self.q_off = torch.zeros(R + 1, dtype=torch.int32, device=dev)
-        self.ctx_off = torch.zeros(R + 1, dtype=torch.int64, device=dev)
-        self.kpool = self.vpool = None
-        if with_kv:  # match-only sessions never touch the pools
+        self.matched_len = torch.zeros(R, dtype=torch.int32).to(dev)
+        self.page_table = torch.full((R, self.max_blocks), -1, dtype=torch.int32).to(dev)
+        self.q_off = torch.zeros(R + 1, dtype=torch.int32).to(dev)
+        self.ctx_off = torch.zeros(R + 1, dtype=torch.int64).to(dev)
+        self.kpool, self.vpool = kpool, vpool
+        if with_kv and kpool is None:  # match-only sessions never touch the pools
             shape = (w.n_pages, BLOCK, a.n_kv_heads, a.head_dim)
-            self.kpool = torch.empty(shape, dtype=a.torch_dtype, device=dev)
-            self.vpool = torch.empty(shape, dtype=a.torch_dtype, device=dev)
-            w.fill_pool("k", self.kpool)
-            w.fill_pool("v", self.vpool)
+            if host_fill:
+                n = min(w.n_pages, 2048)
+                self.kpool = _tiled_from_host(w.pool_pages("k", 0, n), w.n_pages, dev)
+                self.vpool = _tiled_from_host(w.pool_pages("v", 0, n), w.n_pages, dev)
+            else:
+                self.kpool = torch.empty(shape, dtype=a.torch_dtype, device=dev)
+                self.vpool = torch.empty(shape, dtype=a.torch_dtype, device=dev)
+                w.fill_pool("k", self.kpool)
+                w.fill_pool("v", self.vpool)
         self.q = None
 
     # -- one-off: lay out Q / K_new / V_new for the suffixes this workload's match leaves uncached
@@ -44,15 +65,25 @@ class Session:
         torch.cuda.synchronize(dev)
         ml = self.matched_len.cpu().numpy()
         self.host_matched_len = ml
-        self.q = w.suffix_rows("q", ml, dev)
-        self.knew = w.suffix_rows("k", ml, dev)
-        self.vnew = w.suffix_rows("v", ml, dev)
-        self.out = torch.zeros_like(self.q)
         n_ctx = max(int(ml.sum()), BLOCK)
-        self.kctx = torch.zeros((n_ctx, a.n_kv_heads, a.head_dim), dtype=a.torch_dtype, device=dev)
-        self.vctx = torch.zeros_like(self.kctx)
+        if self.host_fill:
+            total = int((np.diff(w.req_off) - ml).sum())
+            n = min(max(total, 1), 4096)
+            self.q = _tiled_from_host(w.token_rows("q", 0, n), total, dev)
+            self.knew = _tiled_from_host(w.token_rows("k", 0, n), total, dev)
+            self.vnew = _tiled_from_host(w.token_rows("v", 0, n), total, dev)
+            self.out = torch.empty_like(self.q)
+            self.kctx = torch.empty((n_ctx, a.n_kv_heads, a.head_dim), dtype=a.torch_dtype, device=dev)
+            self.vctx = torch.empty_like(self.kctx)
+        else:
+            self.q = w.suffix_rows("q", ml, dev)
+            self.knew = w.suffix_rows("k", ml, dev)
+            self.vnew = w.suffix_rows("v", ml, dev)
+            self.out = torch.zeros_like(self.q)
+            self.kctx = torch.zeros((n_ctx, a.n_kv_heads, a.head_dim), dtype=a.torch_dtype, device=dev)
+            self.vctx = torch.zeros_like(self.kctx)
         nbytes = skv.skv_prefill_attn_workspace_size(self.desc, w.n_req, self.q.shape[0])
-        self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+        self.workspace = torch.zeros(nbytes, dtype=torch.uint8).to(dev)
         skv.skv_counters_reset(self.tree)
 
     # -- the individual stages (each only enqueues on the current stream)
@@ -100,8 +131,8 @@ class Session:
 
     def counters(self):
         n = self.w.n_in_blocks
-        hit = torch.zeros(max(n, 1), dtype=torch.int32, device=self.device)
-        ucnt = torch.zeros(max(n, 1), dtype=torch.int32, device=self.device)
+        hit = torch.zeros(max(n, 1), dtype=torch.int32).to(self.device)
+        ucnt = torch.zeros(max(n, 1), dtype=torch.int32).to(self.device)
         skv.skv_counters_read(self.tree, hit, ucnt)
         torch.cuda.synchronize(self.device)
         return hit[:n].cpu().numpy().view(np.uint32), ucnt[:n].cpu().numpy().view(np.uint32)
