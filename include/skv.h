@@ -16,8 +16,8 @@
  *    the tree slab and the attention workspace, belongs to the caller and must stay valid
  *    until the work enqueued on `stream` has finished.
  *  - Calls only enqueue work on `stream` and return; they do not synchronise, except the
- *    host-driven structure changes skv_tree_build, skv_tree_insert, skv_evict and skv_tree_compact,
- *    which return after their uploads have completed.
+ *    host-driven structure changes skv_tree_build, skv_tree_insert and skv_evict, which return after their
+ *    uploads have completed, and skv_match_limits_read, which returns a host value.
  *  - Every function returns SKV_OK (0) or a negative error code; nothing is enqueued when
  *    an error is returned.  Arguments that live on the device (offsets, tenants, page ids)
  *    cannot be validated by the host: kernels clamp or skip values that are out of range
@@ -109,8 +109,9 @@ int skv_tree_build(const skv_tree_desc* desc, void* d_slab, size_t bytes, void* 
  * same block; from the first such insertion on skv_match follows every copy whose first block the tenant
  * may see and returns the longest path (equally long ones: the path through the copy with the smaller
  * input block id at the first difference).  Its search explores at most 10 such branch points per request
- * exhaustively, 64 copies per position and 4096 root-to-end walks; beyond those limits the oldest visible
- * copy is taken.  This mode reads the visibility bits back from the device first.
+ * exhaustively, the 64 oldest visible copies per position and 4096 root-to-end walks; a request that runs into one
+ * of these limits may be given a shorter path than the longest one, and the limit is recorded (skv_match_limits_read).
+ * This mode reads the visibility bits back from the device first.
  * New entries receive the input
  * block ids n_in_blocks, n_in_blocks + 1, ... in that order, start with zeroed counters, and are visible to
  * skv_match calls enqueued afterwards.  first_inserted[r] / n_inserted[r] report the index of the request's
@@ -174,6 +175,16 @@ void skv_tree_destroy(skv_tree* tree);
 int skv_match(skv_tree* tree, int32_t n_req, const int32_t* d_req_off, const int32_t* d_req_tokens,
               const int32_t* d_req_tenant, int32_t max_blocks, int32_t* d_matched_len,
               int32_t* d_page_table, void* stream);
+
+/* Limits of the branching lookup (trees with per-tenant copies, Section 4.1): which of them any request has run
+ * into since the tree was built or the word was last cleared -- SKV_LIMIT_BRANCH_POINTS (more than 10 positions
+ * with several visible copies on one walk), SKV_LIMIT_COPIES (more than 64 visible copies at one position),
+ * SKV_LIMIT_WALKS (more than 4096 walks for one request).  0 means every result so far is the longest visible
+ * path.  limits_hit is a HOST word; clear != 0 resets the record.  Synchronises `stream`. */
+#define SKV_LIMIT_BRANCH_POINTS 1u
+#define SKV_LIMIT_COPIES 2u
+#define SKV_LIMIT_WALKS 4u
+int skv_match_limits_read(skv_tree* tree, uint32_t* limits_hit, int32_t clear, void* stream);
 
 /* Current-window counters per input block id (Section 4.2.2: hit_cur and u_cnt;
  * RDR = u_cnt / hit_cur): d_hit[b] = hits, d_ucnt[b] = distinct tenants.  Both arrays have

@@ -16,9 +16,10 @@ LIB_PATH = os.path.join(_HERE, "libskv.so")
 BLOCK = 16
 SKV_F32, SKV_BF16 = 0, 1
 SKV_OK, SKV_EINVAL, SKV_ENOMEM, SKV_ERANGE, SKV_EHIP = 0, -1, -2, -3, -4
+SKV_LIMIT_BRANCH_POINTS, SKV_LIMIT_COPIES, SKV_LIMIT_WALKS = 1, 2, 4
 
 EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_size_for_capacity", "skv_tree_build", "skv_tree_insert", "skv_set_epoch", "skv_block_epochs_read", "skv_evict",
-           "skv_tree_info", "skv_tree_destroy", "skv_match", "skv_counters_read",
+           "skv_tree_info", "skv_tree_destroy", "skv_match", "skv_match_limits_read", "skv_counters_read",
            "skv_counters_reset", "skv_window_roll", "skv_promote", "skv_block_state_read", "skv_suffix_offsets", "skv_gather_kv",
            "skv_scatter_kv", "skv_stream_copy", "skv_decode_attn_workspace_size", "skv_decode_attn",
            "skv_prefill_attn_workspace_size", "skv_prefill_attn", "skv_prefill_attn_static"]
@@ -89,6 +90,7 @@ def lib():
         l.skv_prefill_attn_static.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp,
                                               i32, vp, vp]
         l.skv_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
+        l.skv_match_limits_read.argtypes = [vp, C.POINTER(C.c_uint32), i32, vp]
         _lib = l
     return _lib
 
@@ -220,6 +222,13 @@ def skv_match(tree: Tree, req_off, req_tokens, req_tenant, max_blocks, matched_l
     assert page_table.numel() >= n_req * max_blocks
     _check(lib().skv_match(tree.handle, n_req, _dptr(req_off), _dptr(req_tokens), _dptr(req_tenant),
                            max_blocks, _dptr(matched_len), _dptr(page_table), _stream(stream)), "skv_match")
+
+
+def skv_match_limits_read(tree: Tree, clear=True, stream=None) -> int:
+    v = C.c_uint32()
+    with torch.cuda.device(tree.slab.device):
+        _check(lib().skv_match_limits_read(tree.handle, C.byref(v), int(clear), _stream(stream)), "skv_match_limits_read")
+    return v.value
 
 
 def skv_counters_read(tree: Tree, hit, ucnt, stream=None):

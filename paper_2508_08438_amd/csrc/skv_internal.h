@@ -36,6 +36,7 @@ struct SkvTreeDev {
   const int32_t* flat_of; // [n_in_blocks] flat index of the entry an input block created, -1 if none
   uint32_t* ctr;          // [n_blocks][SKV_CTR_STRIDE]
   uint32_t* epoch;        // [n_blocks]   epoch counter value at the block's last access
+  uint32_t* limits;       // [1] SKV_LIMIT_* bits of the limits the branching lookup has run into since the last read
   const SkvNode* nodes;   // [n_nodes+1]
   const SkvSlot* slots;
   int32_t n_blocks, n_nodes, n_tenants, n_pages;  // n_blocks: block records in use, evicted ones (canon < 0) included

@@ -164,8 +164,10 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
 // once per combination of choices, in lexicographic order of the choices (copies ordered by the input block
 // id of their first block), and keeps the first of the longest walks -- the order in which a depth-first
 // search that tries older copies first meets them.  A walk is described by up to kMaxChoice 6-bit ranks
-// packed into one 64-bit word; past that many branch points, or past kMaxCopies copies at one position, the
-// oldest visible copy is taken without alternatives, and at most kMaxWalks walks are made.
+// packed into one 64-bit word; past that many branch points the oldest visible copy is taken without alternatives,
+// of more than kMaxCopies visible copies at one position the kMaxCopies oldest are considered, and at most kMaxWalks
+// walks are made.  A request that runs into one of these limits may get a shorter path than the longest one; the
+// limit's bit is then set in the tree's limits word (skv_match_limits_read), so the caller knows.
 constexpr int kMaxChoice = 10;
 constexpr int kMaxCopies = 64;
 constexpr int kMaxWalks = 4096;
@@ -173,7 +175,7 @@ constexpr int kMaxWalks = 4096;
 // The `want`-th oldest child of `nd` whose first block equals the request block at x and is visible to the
 // tenant; *n_out = how many such children there are.  -1 if none.
 __device__ inline int find_child_ranked(const SkvTreeDev& t, const SkvNode nd, const int32_t* x, int tenant, int lane,
-                                        int want, int* n_out) {
+                                        int want, int* n_out, uint32_t* limits) {
   *n_out = 0;
   if (nd.tab_cap == 0) return -1;
   const uint64_t h = hash_block(x, lane);
@@ -194,10 +196,20 @@ __device__ inline int find_child_ranked(const SkvTreeDev& t, const SkvNode nd, c
       if (block_equal(x, t.tok + (size_t)cfirst * 16, lane)) {
         const int m = uniform(t.meta[cfirst]);
         const bool visible = !(m < 0 && (m & 0x7fffffff) != tenant);
-        if (visible && n < kMaxCopies) {
+        if (visible) {
           const int id = uniform(t.canon[cfirst]);
-          if (lane == n) { my_canon = id; my_child = child; }
-          ++n;
+          if (n < kMaxCopies) {
+            if (lane == n) { my_canon = id; my_child = child; }
+            ++n;
+          } else {   // more copies than lanes: keep the kMaxCopies oldest, and say so
+            *limits |= SKV_LIMIT_COPIES;
+            int worst = my_canon;
+            for (int o = 32; o >= 1; o >>= 1) worst = max(worst, __shfl_xor(worst, o));
+            if (id < worst) {
+              const uint64_t holder = ballot64(my_canon == worst);
+              if (lane == __builtin_ctzll(holder)) { my_canon = id; my_child = child; }
+            }
+          }
         }
       }
       cand &= cand - 1;
@@ -230,6 +242,7 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_copies_kernel(
 
   // One walk under the choices `ranks`: writes the matched blocks' record indices to row[], returns their
   // number; *n_choice / *counts describe the branch points met (how many visible copies each had).
+  uint32_t limits = 0;   // SKV_LIMIT_* bits this request ran into (uniform)
   auto walk = [&](uint64_t ranks, int* n_choice, uint64_t* counts) {
     int j = 0, node = 0, dp = 0;
     uint64_t cnt = 0;
@@ -240,11 +253,15 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_copies_kernel(
       cur.tab_cap = uniform(cur.tab_cap);
       int n = 0;
       const int want = dp < kMaxChoice ? (int)((ranks >> (6 * dp)) & 63) : 0;
-      const int child = find_child_ranked(t, cur, x + (size_t)j * 16, tenant, lane, want, &n);
+      const int child = find_child_ranked(t, cur, x + (size_t)j * 16, tenant, lane, want, &n, &limits);
       if (child < 0) break;
-      if (n >= 2 && dp < kMaxChoice) {
-        cnt |= (uint64_t)(n - 1) << (6 * dp);   // highest rank at this branch point
-        ++dp;
+      if (n >= 2) {
+        if (dp < kMaxChoice) {
+          cnt |= (uint64_t)(n - 1) << (6 * dp);   // highest rank at this branch point
+          ++dp;
+        } else {
+          limits |= SKV_LIMIT_BRANCH_POINTS;
+        }
       }
       SkvNode nd = t.nodes[child];
       const int first = uniform(nd.first);
@@ -286,7 +303,8 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_copies_kernel(
 
   uint64_t ranks = 0, best_ranks = 0;
   int best = -1;
-  for (int walks = 0; walks < kMaxWalks; ++walks) {
+  for (int walks = 0;; ++walks) {
+    if (walks == kMaxWalks) { limits |= SKV_LIMIT_WALKS; break; }
     int dp = 0;
     uint64_t top = 0;
     const int len = walk(ranks, &dp, &top);
@@ -316,6 +334,7 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_copies_kernel(
     t.epoch[blk] = t.cur_epoch;
   }
   if (lane == 0) matched_len[r] = best * SKV_BLOCK_TOKENS;
+  if (lane == 0 && limits) atomicOr(t.limits, limits);
   for (int i = best + lane; i < max_blocks; i += kWave) row[i] = -1;
 }
 
@@ -366,6 +385,21 @@ extern "C" int skv_match(skv_tree* t, int32_t n_req, const int32_t* d_req_off,
     skv_match_kernel<<<grid, kWave * kWavesPerWg, 0, (hipStream_t)stream>>>(
         t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table);
   SKV_HIP(hipGetLastError());
+  return SKV_OK;
+}
+
+extern "C" int skv_match_limits_read(skv_tree* t, uint32_t* limits_hit, int32_t clear, void* stream) {
+  if (!t || !limits_hit) return SKV_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  uint32_t v = 0;
+  SKV_HIP(hipMemcpyAsync(&v, t->dev.limits, sizeof(v), hipMemcpyDeviceToHost, st));
+  SKV_HIP(hipStreamSynchronize(st));
+  if (clear && v) {
+    const uint32_t zero = 0;
+    SKV_HIP(hipMemcpyAsync(t->dev.limits, &zero, sizeof(zero), hipMemcpyHostToDevice, st));
+    SKV_HIP(hipStreamSynchronize(st));
+  }
+  *limits_hit = v;
   return SKV_OK;
 }
 

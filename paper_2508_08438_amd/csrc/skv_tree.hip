@@ -35,7 +35,7 @@ namespace {
 constexpr int64_t kMaxBlocks = 0x7fffffff / 32;
 
 struct Layout {  // byte offsets inside the slab
-  size_t tok, page, meta, canon, flat_of, ctr, epoch, nodes, slots, total;
+  size_t tok, page, meta, canon, flat_of, ctr, epoch, status, nodes, slots, total;
 };
 
 // Every array is sized for `cap` blocks: the entries the build creates plus room for later insertions.
@@ -55,6 +55,7 @@ Layout make_layout(size_t n_blocks, size_t n_in_blocks, size_t n_nodes_incl_root
   l.slots = o; o = skv_align256(o + (n_slots ? n_slots : 1) * sizeof(SkvSlot));
   l.ctr = o;   o = skv_align256(o + n_blocks * SKV_CTR_STRIDE * sizeof(uint32_t));
   l.epoch = o; o = skv_align256(o + (n_blocks ? n_blocks : 1) * sizeof(uint32_t));
+  l.status = o; o = skv_align256(o + 64 * sizeof(uint32_t));   // word 0: limits the branching lookup ran into
   l.total = o;
   return l;
 }
@@ -373,6 +374,7 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   t->dev.flat_of = (const int32_t*)(base + L.flat_of);
   t->dev.ctr = (uint32_t*)(base + L.ctr);
   t->dev.epoch = (uint32_t*)(base + L.epoch);
+  t->dev.limits = (uint32_t*)(base + L.status);
   t->dev.cur_epoch = 0;
   t->dev.nodes = (const SkvNode*)(base + L.nodes);
   t->dev.slots = (const SkvSlot*)(base + L.slots);
@@ -388,6 +390,10 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
     size_t n = (size_t)cap_blocks * SKV_CTR_STRIDE;
     fill_u32_kernel<<<grid_for(n, 256), 256, 0, st>>>(t->dev.ctr, n, 0u);
     fill_u32_kernel<<<grid_for((size_t)cap_blocks, 256), 256, 0, st>>>(t->dev.epoch, (size_t)cap_blocks, 0u);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) {
+    fill_u32_kernel<<<1, 64, 0, st>>>(t->dev.limits, 64, 0u);
     e = hipGetLastError();
   }
   if (e == hipSuccess) e = hipStreamSynchronize(st);

@@ -165,3 +165,14 @@ def test_static_scratch_attention_rejects_oversized_batches_before_touching_the_
     args[0] = None
     assert l.skv_prefill_attn_static(C.byref(good), 4, *args) == -1          # null tensor
     assert l.skv_prefill_attn_static(None, 4, *args) == -1
+
+
+def test_limits_read_and_stream_copy_argument_checks(skv):
+    l = skv.lib()
+    v = C.c_uint32()
+    assert l.skv_match_limits_read(None, C.byref(v), 1, None) == -1
+    fake = C.c_void_p(1 << 20)
+    assert l.skv_stream_copy(fake, fake, 0, None) == 0                 # nothing to copy
+    assert l.skv_stream_copy(None, fake, 64, None) == -1
+    assert l.skv_stream_copy(fake, fake, 24, None) == -1               # not a multiple of 16
+    assert l.skv_stream_copy(C.c_void_p((1 << 20) + 4), fake, 64, None) == -1

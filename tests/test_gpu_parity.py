@@ -78,6 +78,24 @@ def test_match_empty_tree_and_empty_batch():
     torch.cuda.synchronize()
 
 
+def test_match_clamps_requests_longer_than_the_page_table_row():
+    """max_blocks smaller than a request's block count: the first max_blocks blocks are considered, as the oracle's
+    cap does; lengths, page ids and counters agree."""
+    skv = _skv()
+    cases = [(inputs.small_random(seed=s, n_req=24, p_sens=0.2), 2) for s in range(20)]
+    cases += [(inputs.config2(), 10), (inputs.config4(), 100), (inputs.config3(), 7)]
+    for w, cap in cases:
+        assert w.max_blocks > cap or w.n_req == 0 or "small" in w.name
+        tree = skv.skv_tree_build(w.seq_tokens, w.seq_off, w.blk_sensitive, w.blk_owner, w.blk_page, w.n_tenants,
+                                  w.n_pages, device="cuda:0")
+        mlen, pt = device_match(skv, tree, w.req_off, w.req_tokens, w.req_tenant, cap)
+        otree = oracle.OracleTree.from_workload(w)
+        o_mlen, o_pt = otree.match(w.req_off, w.req_tokens, w.req_tenant, cap)
+        assert (o_mlen <= cap * B).all() and (o_mlen == cap * B).any(), w.name    # the cap bites
+        assert np.array_equal(mlen, o_mlen) and np.array_equal(pt, o_pt), w.name
+        compare_state(skv, tree, otree, w.name)
+
+
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
 def test_match_configs_full_size(name):
     if name == "c5":
@@ -208,12 +226,22 @@ def test_pipeline_config3_streaming_mix():
 
 
 def test_pipeline_config4_long_context():
-    check_pipeline(inputs.config4(), "c4", n_sample=1024, n_sub_req=4)
-    check_pipeline(inputs.config4(hard=True), "c4_hard", n_sample=512, n_sub_req=2)
+    check_pipeline(inputs.config4(), "c4", n_sample=4096, n_sub_req=4)
+    check_pipeline(inputs.config4(hard=True), "c4_hard", n_sample=4096, n_sub_req=2)
 
 
 def test_pipeline_config5_sweep_quarter_sensitive():
     check_pipeline(inputs.config5(0.25), "c5@0.25", n_sample=4096, n_sub_req=24)
+
+
+def test_pipeline_config5_sweep_no_sensitive_blocks():
+    # the one setting of the sweep with long reused prefixes (88.7 % of the prompt tokens)
+    check_pipeline(inputs.config5(0.0), "c5@0", n_sample=4096, n_sub_req=8)
+
+
+@pytest.mark.parametrize("p", [0.5, 1.0])
+def test_pipeline_config5_sweep_half_and_all_sensitive(p):
+    check_pipeline(inputs.config5(p), f"c5@{p}", n_sample=4096, n_sub_req=4)
 
 
 # ---- attention alone, on shapes the configs do not reach ---------------------------------------
@@ -887,6 +915,74 @@ def test_private_copy_lookup_backtracks():
     otree.match(off, req, t1, 2)
     assert ml[0] == 2 * B and list(pt[0]) == [20, 21]
     compare_state(skv, dtree, otree, "backtrack")
+
+
+def test_branching_lookup_reports_its_limits():
+    """More visible copies at one position than the lookup ranks, and more branch points / walks than it explores:
+    the limits word says so; inside the limits it stays zero and results equal the oracle's."""
+    skv = _skv()
+    blocks = lambda *ids: np.concatenate([np.full(B, i, np.int32) for i in ids])
+    T = 100
+    # (a) 70 tenants each cache their own copy of the same two blocks below an empty tree; all copies are promoted
+    args = (np.zeros(0, np.int32), np.zeros(1, np.int64), np.zeros(0, np.uint8), np.zeros(0, np.int32), np.zeros(0, np.int32))
+    off = np.array([0, 2 * B], np.int32)
+    for n_copies, want_flag in ((64, 0), (70, skv.SKV_LIMIT_COPIES)):
+        otree = oracle.OracleTree(*args)
+        dtree = skv.skv_tree_build(*args, T, 4096, device="cuda:0", reserve_blocks=1024)
+        assert skv.skv_match_limits_read(dtree) == 0
+        for c in range(n_copies):
+            ten = np.array([c], np.int32)
+            mlen, _ = device_match(skv, dtree, off, blocks(7, 8), ten, 2)
+            assert mlen[0] == 0        # the copies of the others are private
+            pages = np.array([[2 * c, 2 * c + 1]], np.int32)
+            skv.skv_tree_insert(dtree, off, blocks(7, 8), ten, mlen, pages, private_copies=True)
+            otree.insert(off, blocks(7, 8), ten, mlen, pages, private_copies=True)
+        assert skv.skv_match_limits_read(dtree) == 0       # each tenant saw one visible copy at most
+        ids = np.arange(otree.n_in_blocks, dtype=np.int32)
+        skv.skv_promote(dtree, _dev(ids))
+        otree.promote(ids)
+        ml, pt = device_match(skv, dtree, off, blocks(7, 8), np.array([99], np.int32), 2)
+        o_ml, o_pt = otree.match(off, blocks(7, 8), np.array([99], np.int32), 2)
+        assert np.array_equal(ml, o_ml) and np.array_equal(pt, o_pt), n_copies    # equally long paths: the oldest copy
+        assert skv.skv_match_limits_read(dtree) == want_flag, n_copies
+        assert skv.skv_match_limits_read(dtree) == 0                                  # reading cleared it
+    # (b) a ladder: every round one more position of the same 14-block sequence gets a second visible copy
+    otree = oracle.OracleTree(*args)
+    dtree = skv.skv_tree_build(*args, T, 4096, device="cuda:0", reserve_blocks=1024)
+    seq = blocks(*range(20, 34))
+    off = np.array([0, 14 * B], np.int32)
+    page = 0
+    hit_limit_at = None
+    pos_of_id, promoted = {}, set()
+    for rnd in range(14):
+        ten = np.array([rnd], np.int32)
+        mlen, _ = device_match(skv, dtree, off, seq, ten, 14)
+        flags = skv.skv_match_limits_read(dtree)
+        o_mlen, _ = otree.match(off, seq, ten, 14)
+        if flags == 0:
+            assert np.array_equal(mlen, o_mlen), rnd
+        elif hit_limit_at is None:
+            hit_limit_at = rnd
+        # insert with the oracle's matched length, so that both sides build the same tree whatever the device found
+        n_new = 14 - int(o_mlen[0]) // B
+        pages = np.full((1, 14), -1, np.int32)
+        pages[0, :n_new] = np.arange(page, page + n_new)
+        page += n_new
+        first, n = skv.skv_tree_insert(dtree, off, seq, ten, o_mlen, pages, private_copies=True)
+        o_first, o_n = otree.insert(off, seq, ten, o_mlen, pages, private_copies=True)
+        assert np.array_equal(first, o_first) and np.array_equal(n, o_n), rnd
+        base_id = otree.n_in_blocks - int(n[0])
+        for k in range(int(n[0])):
+            pos_of_id[base_id + k] = int(first[0]) + k     # first_inserted: index of the request's first new block
+        # the verifier clears every copy's blocks up to position rnd + 1: one more position with several visible copies
+        ids = np.array([i for i, pos in pos_of_id.items() if pos <= rnd + 1 and i not in promoted], np.int32)
+        if len(ids):
+            skv.skv_promote(dtree, _dev(ids))
+            otree.promote(ids)
+            promoted.update(int(i) for i in ids)
+        skv.skv_match_limits_read(dtree)
+    print(f"[limits] ladder: first limit reported in round {hit_limit_at}", flush=True)
+    assert hit_limit_at is not None and hit_limit_at >= 8
 
 
 def test_private_copies_config3_full_size():
