@@ -1,4 +1,4 @@
-// Longest visible prefix match + access-monitor update, one wavefront per request.
+// Longest visible prefix match + access-monitor update, one workgroup of four wavefronts per request.
 //
 // SafeKV Section 4.3.1 (Search): the lookup walks the prefix path and checks private_tag at
 // every hop; a private entry may only be used by its creator_id, otherwise the walk stops.
@@ -10,7 +10,8 @@
 // the node's contiguous token span; a ballot of the mismatches gives the first block that
 // differs, a second ballot over the blocks' metadata gives the first block the tenant may
 // not see; the smaller of the two ends the walk.  The lanes of the matched blocks then copy
-// the page ids and issue the counter atomics.
+// the page ids and issue the counter atomics.  The four wavefronts of a workgroup take
+// disjoint parts of a long node's span and combine their stop positions through LDS.
 #include "skv_internal.h"
 
 namespace {
@@ -19,6 +20,8 @@ constexpr int kWave = 64;
 constexpr int kWavesPerWg = 4;
 constexpr int kSub = 4;                    // 256-token sub-windows per step: one 16-byte vector (4 tokens) per lane each
 constexpr int kStepBlocks = kSub * 16;     // 64 blocks (1024 tokens) per step: one block per lane for metadata and page ids
+constexpr int kAhead = 4;                  // steps of a node whose loads are in flight together
+constexpr int kCoopMaxRequests = 512;      // batches up to this size give every request a whole workgroup
 typedef int32_t tok4 __attribute__((ext_vector_type(4), aligned(4)));   // request offsets are token-, not 16-byte aligned
 
 __device__ inline uint64_t ballot64(bool p) { return __ballot(p); }
@@ -72,13 +75,23 @@ __device__ inline int find_child(const SkvTreeDev& t, const SkvNode nd, const in
   return -1;
 }
 
+// kCoop = kWavesPerWg: one workgroup of four wavefronts per request (few requests: their long nodes set the time).
+// kCoop = 1: one wavefront per request, four requests per workgroup, no exchange (many requests: throughput).
+// In the cooperative form all four walk the same path (each finds the same child at a node:
+// no exchange needed); a node's span is compared in rounds of kWavesPerWg groups of kAhead steps, one group per
+// wavefront, whose first mismatch or invisible block is combined through LDS into the round's stop position.  Each
+// wavefront then records (page ids, counters, epochs) the blocks of its own group that lie before that position.
+// Every branch around a barrier depends only on values that are equal in all four wavefronts.
+template <int kCoop>
 __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
     SkvTreeDev t, int n_req, const int32_t* __restrict__ req_off, const int32_t* __restrict__ req_tok,
     const int32_t* __restrict__ req_tenant, int max_blocks, int32_t* __restrict__ matched_len,
     int32_t* __restrict__ page_table) {
+  __shared__ int stop_at[2][kWavesPerWg];   // per round parity and wavefront: blocks of the node matched before its stop
   const int lane = threadIdx.x & (kWave - 1);
-  const int r = blockIdx.x * kWavesPerWg + (threadIdx.x >> 6);
-  if (r >= n_req) return;  // whole wave leaves; the kernel has no barriers
+  const int wave = kCoop > 1 ? uniform(threadIdx.x >> 6) : 0;   // wavefront within the request's team
+  const int r = kCoop > 1 ? blockIdx.x : blockIdx.x * kWavesPerWg + (threadIdx.x >> 6);
+  if (kCoop == 1 && r >= n_req) return;  // whole wave leaves; this form has no barriers
   const int lo = uniform(req_off[r]), hi = uniform(req_off[r + 1]);
   const int tenant = uniform(req_tenant[r]);
   int nb = hi > lo ? (hi - lo) / SKV_BLOCK_TOKENS : 0;
@@ -88,9 +101,12 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
   int32_t* row = page_table + (size_t)r * max_blocks;
   const uint32_t tbit = 1u << (tenant & 31);
   const int tword = 1 + (tenant >> 5);
+  constexpr int kGroup = kAhead * kStepBlocks;        // blocks one wavefront compares per round
+  constexpr int kRound = kCoop * kGroup;
 
   int j = 0;      // blocks matched so far
   int node = 0;   // current node (root)
+  int parity = 0;
   bool stop = false;
   while (j < nb && !stop) {
     SkvNode cur = t.nodes[node];
@@ -102,59 +118,97 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
     const int first = uniform(nd.first);
     const int nblk = uniform(nd.n_blocks);
     const int span = min(nblk, nb - j);  // blocks of this node the request can still cover
-    // The tokens and metadata of step c+1 are requested before step c is compared, so the walk down a long
-    // compressed node pays one memory latency per two steps instead of one per step.
-    tok4 a[kSub], b[kSub], a2[kSub], b2[kSub];
-    int m = 0, m2 = 0, pg = 0, pg2 = 0;   // per-block metadata word and page id of the lane's block
-    const int jn = j;   // request block that faces the node's first block
-    auto fetch = [&](int c, tok4* aa, tok4* bb, int& mm, int& pp) __attribute__((always_inline)) {
-      const int cb = min(kStepBlocks, span - c);
-      const int ntok = cb * 16;
-      const tok4* tt = (const tok4*)(t.tok + (size_t)(first + c) * 16);
-      const tok4* xx = (const tok4*)(x + (size_t)(jn + c) * 16);
-      const tok4 z = {0, 0, 0, 0};
+    const int jn = j;                    // request block that faces the node's first block
+    for (int r0 = 0; r0 < span && !stop; r0 += kRound) {
+      // A node's span is contiguous, so the addresses of all steps are known at once: the loads of this wavefront's
+      // kAhead steps (tokens of both sides, metadata, page ids) are issued together, then compared.
+      const int g0 = r0 + wave * kGroup;            // first block (within the node) of this wavefront's group
+      const int g1 = min(span, g0 + kGroup);
+      tok4 a[kAhead][kSub], b[kAhead][kSub];
+      int m[kAhead], pg[kAhead];   // per-block metadata word and page id of the lane's block
 #pragma unroll
-      for (int u = 0; u < kSub; ++u) {
-        const int i = u * kWave + lane;      // vector index: tokens 4 i .. 4 i + 3, block i / 4
-        aa[u] = 4 * i < ntok ? xx[i] : z;
-        bb[u] = 4 * i < ntok ? tt[i] : z;
-      }
-      mm = lane < cb ? t.meta[first + c + lane] : 0;
-      pp = lane < cb ? t.page[first + c + lane] : 0;
-    };
-    if (span > 0) fetch(0, a, b, m, pg);
-    for (int c = 0; c < span && !stop; c += kStepBlocks) {
-      const int cb = min(kStepBlocks, span - c);
-      if (c + kStepBlocks < span) fetch(c + kStepBlocks, a2, b2, m2, pg2);
-      int n_eq = cb;  // leading blocks whose tokens all agree
+      for (int s = 0; s < kAhead; ++s) {
+        const int c = g0 + s * kStepBlocks;
+        if (c < g1) {
+          const int cb = min(kStepBlocks, g1 - c);
+          const int ntok = cb * 16;
+          const tok4* tt = (const tok4*)(t.tok + (size_t)(first + c) * 16);
+          const tok4* xx = (const tok4*)(x + (size_t)(jn + c) * 16);
+          const tok4 z = {0, 0, 0, 0};
 #pragma unroll
-      for (int u = kSub - 1; u >= 0; --u) {
-        const uint64_t ne = ballot64(differ(a[u], b[u]));
-        if (ne) n_eq = u * 16 + (__builtin_ctzll(ne) >> 2);
+          for (int u = 0; u < kSub; ++u) {
+            const int i = u * kWave + lane;      // vector index: tokens 4 i .. 4 i + 3, block i / 4
+            a[s][u] = 4 * i < ntok ? xx[i] : z;
+            b[s][u] = 4 * i < ntok ? tt[i] : z;
+          }
+          m[s] = lane < cb ? t.meta[first + c + lane] : 0;
+          pg[s] = lane < cb ? t.page[first + c + lane] : 0;
+        }
       }
-      // visibility rule: private (bit 31) entries only for their creator
-      const uint64_t hidden = ballot64(m < 0 && (m & 0x7fffffff) != tenant);
-      const int n_vis = hidden ? __builtin_ctzll(hidden) : cb;
-      const int take = min(n_eq, n_vis);
-      if (lane < take) {
-        const int blk = first + c + lane;
-        row[j + lane] = pg;
-        uint32_t* ctr = t.ctr + (size_t)blk * SKV_CTR_STRIDE;
-        atomicAdd(ctr, 1u);
-        atomicOr(ctr + tword, tbit);
-        t.epoch[blk] = t.cur_epoch;  // every lookup of one batch writes the same value
-      }
-      j += take;
-      if (take < cb) stop = true;
+      int good = g1 > g0 ? g1 - g0 : 0;   // leading blocks of the group that match and are visible
+      bool open = true;
 #pragma unroll
-      for (int u = 0; u < kSub; ++u) { a[u] = a2[u]; b[u] = b2[u]; }
-      m = m2;
-      pg = pg2;
+      for (int s = 0; s < kAhead; ++s) {
+        const int c = g0 + s * kStepBlocks;
+        if (c < g1 && open) {
+          const int cb = min(kStepBlocks, g1 - c);
+          int n_eq = cb;  // leading blocks whose tokens all agree
+#pragma unroll
+          for (int u = kSub - 1; u >= 0; --u) {
+            const uint64_t ne = ballot64(differ(a[s][u], b[s][u]));
+            if (ne) n_eq = u * 16 + (__builtin_ctzll(ne) >> 2);
+          }
+          // visibility rule: private (bit 31) entries only for their creator
+          const uint64_t hidden = ballot64(m[s] < 0 && (m[s] & 0x7fffffff) != tenant);
+          const int n_vis = hidden ? __builtin_ctzll(hidden) : cb;
+          const int take = min(n_eq, n_vis);
+          if (take < cb) {
+            good = s * kStepBlocks + take;
+            open = false;
+          }
+        }
+      }
+      // the round's stop: the first group that ends early ends the walk there
+      int upto = r0;         // blocks of the node matched once this round is done
+      bool ended = false;
+      if (kCoop > 1) {
+        if (lane == 0) stop_at[parity][wave] = good;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kCoop; ++w) {
+          const int w0 = r0 + w * kGroup, w1 = min(span, w0 + kGroup);
+          if (!ended && w0 < span) {
+            const int gw = stop_at[parity][w];
+            upto = w0 + gw;
+            if (gw < w1 - w0) ended = true;
+          }
+        }
+        parity ^= 1;         // the other row takes the next round: no second barrier is needed
+      } else {
+        upto = g0 + good;
+        ended = good < g1 - g0;
+      }
+      // record this wavefront's blocks that lie before the stop
+      const int mine = min(upto, g1) - g0;
+#pragma unroll
+      for (int s = 0; s < kAhead; ++s) {
+        const int c = g0 + s * kStepBlocks;
+        if (c + lane < g0 + mine) {
+          const int blk = first + c + lane;
+          row[jn + c + lane] = pg[s];
+          uint32_t* ctr = t.ctr + (size_t)blk * SKV_CTR_STRIDE;
+          atomicAdd(ctr, 1u);
+          atomicOr(ctr + tword, tbit);
+          t.epoch[blk] = t.cur_epoch;  // every lookup of one batch writes the same value
+        }
+      }
+      j = jn + upto;
+      if (ended) stop = true;
     }
     node = child;
   }
-  if (lane == 0) matched_len[r] = j * SKV_BLOCK_TOKENS;
-  for (int i = j + lane; i < max_blocks; i += kWave) row[i] = -1;
+  if (wave == 0 && lane == 0) matched_len[r] = j * SKV_BLOCK_TOKENS;
+  for (int i = j + wave * kWave + lane; i < max_blocks; i += kWave * kCoop) row[i] = -1;
 }
 
 // ---- lookup on a tree with per-tenant copies ---------------------------------------------------------
@@ -381,8 +435,11 @@ extern "C" int skv_match(skv_tree* t, int32_t n_req, const int32_t* d_req_off,
   if (t->has_copies)
     skv_match_copies_kernel<<<grid, kWave * kWavesPerWg, 0, (hipStream_t)stream>>>(
         t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table);
+  else if (n_req <= kCoopMaxRequests)   // few requests: a workgroup each
+    skv_match_kernel<kWavesPerWg><<<n_req, kWave * kWavesPerWg, 0, (hipStream_t)stream>>>(
+        t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table);
   else
-    skv_match_kernel<<<grid, kWave * kWavesPerWg, 0, (hipStream_t)stream>>>(
+    skv_match_kernel<1><<<grid, kWave * kWavesPerWg, 0, (hipStream_t)stream>>>(
         t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table);
   SKV_HIP(hipGetLastError());
   return SKV_OK;
