@@ -16,8 +16,8 @@
  *    the tree slab and the attention workspace, belongs to the caller and must stay valid
  *    until the work enqueued on `stream` has finished.
  *  - Calls only enqueue work on `stream` and return; they do not synchronise, except the
- *    host-driven structure changes skv_tree_build, skv_tree_insert and skv_evict, which return after their
- *    uploads have completed, and skv_match_limits_read, which returns a host value.
+ *    host-driven structure changes skv_tree_build, skv_tree_insert, skv_evict and skv_tree_compact, which
+ *    return after their uploads have completed, and skv_match_limits_read, which returns a host value.
  *  - Every function returns SKV_OK (0) or a negative error code; nothing is enqueued when
  *    an error is returned.  Arguments that live on the device (offsets, tenants, page ids)
  *    cannot be validated by the host: kernels clamp or skip values that are out of range
@@ -144,11 +144,22 @@ int skv_block_epochs_read(skv_tree* tree, uint32_t* d_epoch, void* stream);
  * (HOST arrays of n_want entries) receive the removed blocks and their pool pages in removal order, so the
  * caller can hand the pages out again; *n_evicted their number.  Removed blocks read as absent from then on
  * (skv_counters_read and skv_block_state_read report them like blocks without entry); their record space in
- * the slab is not reused.  Reads the epochs back from the device and uploads the changed records on
+ * the slab is reused after skv_tree_compact.  Reads the epochs back from the device and uploads the changed records on
  * `stream`, synchronising it; must not overlap with other calls on the tree.
  * Errors: SKV_EINVAL for null pointers or negative counts. */
 int skv_evict(skv_tree* tree, int64_t n_want, const int32_t* protect_ids, int64_t n_protect,
               int32_t* evicted_ids, int32_t* evicted_pages, int64_t* n_evicted, void* stream);
+
+/* Reclaim the record space that evictions and insertions leave behind (Section 4.3.2 Progressive Eviction: a
+ * compressed chain's address vector shrinks as its entries are released, and the chain is removed once it is
+ * empty): evicted block records, emptied nodes, abandoned child tables.  The live structure is laid out afresh in
+ * the same slab, and the input block ids are renumbered densely in their old order: id_map (HOST, one entry per
+ * input block id before the call) receives each id's new value, -1 for blocks that no longer exist;
+ * *n_in_blocks_after (may be NULL) the new id count.  Lookups, counters, visibility bits and epochs are unchanged
+ * apart from the renumbering; the capacity left for skv_tree_insert is the slab's capacity minus the live blocks.
+ * Reads the kernels' per-block state back, uploads the whole structure on `stream` and synchronises it; must not
+ * overlap with other calls on the tree.  Errors: SKV_EINVAL for a null tree or map. */
+int skv_tree_compact(skv_tree* tree, int32_t* id_map, int64_t* n_in_blocks_after, void* stream);
 
 /* n_nodes: compressed nodes (root excluded); n_blocks: distinct cached blocks (evicted ones not counted);
  * n_in_blocks: blocks in the description (repeats included).  Any pointer may be NULL. */

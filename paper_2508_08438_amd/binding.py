@@ -18,7 +18,7 @@ SKV_F32, SKV_BF16 = 0, 1
 SKV_OK, SKV_EINVAL, SKV_ENOMEM, SKV_ERANGE, SKV_EHIP = 0, -1, -2, -3, -4
 SKV_LIMIT_BRANCH_POINTS, SKV_LIMIT_COPIES, SKV_LIMIT_WALKS = 1, 2, 4
 
-EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_size_for_capacity", "skv_tree_build", "skv_tree_insert", "skv_set_epoch", "skv_block_epochs_read", "skv_evict",
+EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_size_for_capacity", "skv_tree_build", "skv_tree_insert", "skv_set_epoch", "skv_block_epochs_read", "skv_evict", "skv_tree_compact",
            "skv_tree_info", "skv_tree_destroy", "skv_match", "skv_match_limits_read", "skv_counters_read",
            "skv_counters_reset", "skv_window_roll", "skv_promote", "skv_block_state_read", "skv_suffix_offsets", "skv_gather_kv",
            "skv_scatter_kv", "skv_stream_copy", "skv_decode_attn_workspace_size", "skv_decode_attn",
@@ -90,6 +90,7 @@ def lib():
         l.skv_prefill_attn_static.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp,
                                               i32, vp, vp]
         l.skv_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
+        l.skv_tree_compact.argtypes = [vp, vp, C.POINTER(i64), vp]
         l.skv_match_limits_read.argtypes = [vp, C.POINTER(C.c_uint32), i32, vp]
         _lib = l
     return _lib
@@ -212,6 +213,17 @@ def skv_evict(tree: Tree, n_want: int, protect_ids=(), stream=None):
         _check(lib().skv_evict(tree.handle, n_want, hp(prot), len(prot), hp(ids), hp(pages), C.byref(k),
                                _stream(stream)), "skv_evict")
     return ids[: k.value], pages[: k.value]
+
+
+def skv_tree_compact(tree: Tree, stream=None):
+    """Returns id_map (numpy int32, old input block id -> new id, -1 if gone)."""
+    n = tree.info()["n_in_blocks"]
+    id_map = np.full(max(n, 1), -1, dtype=np.int32)
+    after = C.c_int64()
+    with torch.cuda.device(tree.slab.device):
+        _check(lib().skv_tree_compact(tree.handle, C.c_void_p(id_map.ctypes.data), C.byref(after), _stream(stream)),
+               "skv_tree_compact")
+    return id_map[:n]
 
 
 def skv_match(tree: Tree, req_off, req_tokens, req_tenant, max_blocks, matched_len, page_table, stream=None):

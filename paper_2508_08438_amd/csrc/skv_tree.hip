@@ -799,6 +799,126 @@ extern "C" int skv_evict(skv_tree* t, int64_t n_want, const int32_t* protect_ids
   return SKV_OK;
 }
 
+// ---- reclaiming record space (Section 4.3.2 Progressive Eviction: a chain's address vector shrinks as its entries
+// are released and the chain itself goes once the vector is empty) ----
+// Evictions shorten node runs and unlink emptied nodes, insertions abandon outgrown child tables and split runs; the
+// records they leave behind stay in the slab.  Compaction lays the live structure out afresh: nodes in depth-first
+// order with their blocks contiguous, child tables sized for the children they have, input block ids renumbered
+// densely in their old order (so "older copy" and eviction ties still compare the same way).  The per-block state
+// the kernels own (visibility bits, counters, epochs) is read back, permuted with the records and written again.
+extern "C" int skv_tree_compact(skv_tree* t, int32_t* id_map, int64_t* n_in_blocks_after, void* stream) {
+  if (!t || !t->host) return SKV_EINVAL;
+  SkvHostMirror* m = t->host;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t nb_old = t->dev.n_blocks, nin_old = t->n_in_blocks;
+  if (nin_old > 0 && !id_map) return SKV_EINVAL;
+  std::vector<int32_t> meta((size_t)nb_old);
+  std::vector<uint32_t> ctr((size_t)nb_old * SKV_CTR_STRIDE), epoch((size_t)nb_old);
+  if (nb_old) {
+    SKV_HIP(hipMemcpyAsync(meta.data(), t->dev.meta, (size_t)nb_old * 4, hipMemcpyDeviceToHost, st));
+    SKV_HIP(hipMemcpyAsync(ctr.data(), t->dev.ctr, (size_t)nb_old * SKV_CTR_STRIDE * 4, hipMemcpyDeviceToHost, st));
+    SKV_HIP(hipMemcpyAsync(epoch.data(), t->dev.epoch, (size_t)nb_old * 4, hipMemcpyDeviceToHost, st));
+    SKV_HIP(hipStreamSynchronize(st));
+  }
+  // dense input ids, old order kept
+  std::vector<int32_t> new_id((size_t)nin_old, -1);
+  int32_t n_ids = 0;
+  for (int64_t i = 0; i < nin_old; ++i)
+    if (m->flat_of[i] >= 0) new_id[i] = n_ids++;
+  // depth-first relabelling of the nodes that can still be reached; blocks follow their nodes
+  std::vector<SkvNode> nodes;
+  std::vector<int32_t> kids, parent, old_of_new;
+  std::vector<SkvSlot> slots;
+  std::vector<int32_t> tok, canon, page, n_meta, flat_of((size_t)n_ids, -1);
+  std::vector<uint32_t> n_ctr, n_epoch;
+  std::vector<std::pair<int32_t, int32_t>> todo;   // (old node, new parent)
+  todo.push_back({0, -1});
+  std::vector<std::vector<std::pair<uint64_t, int32_t>>> children;   // per new node: (hash, new child) in old table order
+  while (!todo.empty()) {
+    const auto [on, np] = todo.back();
+    todo.pop_back();
+    const SkvNode o = m->nodes[on];
+    const int32_t nn = (int32_t)nodes.size();
+    nodes.push_back(SkvNode{(int32_t)canon.size(), o.n_blocks, 0, 0});
+    kids.push_back(0);
+    parent.push_back(np);
+    children.emplace_back();
+    for (int32_t k = 0; k < o.n_blocks; ++k) {
+      const size_t f = (size_t)o.first + k;
+      flat_of[new_id[m->canon[f]]] = (int32_t)canon.size();
+      canon.push_back(new_id[m->canon[f]]);
+      page.push_back(m->page[f]);
+      n_meta.push_back(meta[f]);
+      n_epoch.push_back(epoch[f]);
+      tok.insert(tok.end(), m->tok.begin() + f * 16, m->tok.begin() + (f + 1) * 16);
+      n_ctr.insert(n_ctr.end(), ctr.begin() + f * SKV_CTR_STRIDE, ctr.begin() + (f + 1) * SKV_CTR_STRIDE);
+    }
+    if (np >= 0) {   // the hash of its first block keys the node in its parent's table
+      const uint64_t h = skv_hash_block_host(&tok[(size_t)nodes[nn].first * 16]);
+      children[np].push_back({h, nn});
+      kids[np]++;
+    }
+    for (int32_t q = o.tab_cap - 1; q >= 0; --q) {
+      const int32_t c = m->slots[(size_t)o.tab_off + q].child;
+      if (c >= 0) todo.push_back({c, nn});
+    }
+  }
+  std::vector<int32_t> filled(nodes.size(), 0);
+  for (size_t n = 0; n < nodes.size(); ++n) {
+    if (children[n].empty()) continue;
+    const uint32_t cap = next_pow2((uint32_t)std::max<size_t>(4, 2 * children[n].size()));
+    nodes[n].tab_off = (int32_t)slots.size();
+    nodes[n].tab_cap = (int32_t)cap;
+    slots.resize(slots.size() + cap, SkvSlot{0, 0, -1, 0});
+    for (const auto& [h, c] : children[n]) {
+      uint32_t q = (uint32_t)h & (cap - 1);
+      while (slots[(size_t)nodes[n].tab_off + q].child >= 0) q = (q + 1) & (cap - 1);
+      slots[(size_t)nodes[n].tab_off + q] = SkvSlot{(uint32_t)h, (uint32_t)(h >> 32), c, 0};
+    }
+    filled[n] = (int32_t)children[n].size();
+  }
+  const int64_t nb = (int64_t)canon.size();
+  if (nb != m->live_blocks) return SKV_EINVAL;   // the mirror lost track of a block: refuse rather than drop it
+  // write everything back; counters and epochs of the free records start from zero again
+  char* base = m->base;
+  const Layout& L = m->L;
+  auto up = [&](size_t off, const void* src, size_t bytes) {
+    return bytes ? hipMemcpyAsync(base + off, src, bytes, hipMemcpyHostToDevice, st) : hipSuccess;
+  };
+  SKV_HIP(up(L.tok, tok.data(), tok.size() * 4));
+  SKV_HIP(up(L.page, page.data(), page.size() * 4));
+  SKV_HIP(up(L.meta, n_meta.data(), n_meta.size() * 4));
+  SKV_HIP(up(L.canon, canon.data(), canon.size() * 4));
+  SKV_HIP(up(L.flat_of, flat_of.data(), flat_of.size() * 4));
+  SKV_HIP(up(L.nodes, nodes.data(), nodes.size() * sizeof(SkvNode)));
+  SKV_HIP(up(L.slots, slots.data(), slots.size() * sizeof(SkvSlot)));
+  SKV_HIP(up(L.ctr, n_ctr.data(), n_ctr.size() * 4));
+  SKV_HIP(up(L.epoch, n_epoch.data(), n_epoch.size() * 4));
+  if (m->cap_blocks > nb) {
+    const size_t n = (size_t)(m->cap_blocks - nb);
+    fill_u32_kernel<<<grid_for(n * SKV_CTR_STRIDE, 256), 256, 0, st>>>(t->dev.ctr + (size_t)nb * SKV_CTR_STRIDE, n * SKV_CTR_STRIDE, 0u);
+    fill_u32_kernel<<<grid_for(n, 256), 256, 0, st>>>(t->dev.epoch + nb, n, 0u);
+    SKV_HIP(hipGetLastError());
+  }
+  SKV_HIP(hipStreamSynchronize(st));
+  for (int64_t i = 0; i < nin_old; ++i) id_map[i] = new_id[i];
+  m->nodes = std::move(nodes);
+  m->kids = std::move(kids);
+  m->filled = std::move(filled);
+  m->parent = std::move(parent);
+  m->slots = std::move(slots);
+  m->slots_used = m->slots.size();
+  m->tok = std::move(tok);
+  m->canon = std::move(canon);
+  m->page = std::move(page);
+  m->flat_of = std::move(flat_of);
+  t->dev.n_blocks = (int32_t)nb;
+  t->dev.n_nodes = (int32_t)m->nodes.size() - 1;
+  t->n_in_blocks = n_ids;
+  if (n_in_blocks_after) *n_in_blocks_after = n_ids;
+  return SKV_OK;
+}
+
 extern "C" int skv_tree_info(const skv_tree* t, int64_t* n_nodes, int64_t* n_blocks, int64_t* n_in_blocks) {
   if (!t) return SKV_EINVAL;
   if (n_nodes) *n_nodes = t->dev.n_nodes;

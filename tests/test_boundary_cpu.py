@@ -171,6 +171,7 @@ def test_limits_read_and_stream_copy_argument_checks(skv):
     l = skv.lib()
     v = C.c_uint32()
     assert l.skv_match_limits_read(None, C.byref(v), 1, None) == -1
+    assert l.skv_tree_compact(None, None, None, None) == -1
     fake = C.c_void_p(1 << 20)
     assert l.skv_stream_copy(fake, fake, 0, None) == 0                 # nothing to copy
     assert l.skv_stream_copy(None, fake, 64, None) == -1

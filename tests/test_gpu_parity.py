@@ -815,6 +815,146 @@ def test_evict_config3_then_reinsert():
 
 
 # ---------------------------------------------------------------------------------------------
+# reclaiming record space (Section 4.3.2 progressive eviction): a tree with little spare room lives through many
+# times its capacity in evictions and insertions; when the slab is full it is compacted and the insert repeated.
+# The oracle never renumbers, so device block ids are translated through the maps the compactions returned.
+
+def run_compact_stream(seed, n_rounds, copies, reserve=96, n_req=10):
+    from test_oracle_insert import make_round
+    skv = _skv()
+    block_vocab = 3 if seed % 3 == 0 else None
+    w = inputs.small_random(seed=seed, n_req=8, p_sens=0.4, n_tenants=3, block_vocab=block_vocab)
+    vocab = int(w.seq_tokens.max()) + 1 if len(w.seq_tokens) else 2
+    n_pages = w.n_pages + 1024
+    otree = oracle.OracleTree.from_workload(w)
+    dtree = skv.skv_tree_build(w.seq_tokens, w.seq_off, w.blk_sensitive, w.blk_owner, w.blk_page, w.n_tenants,
+                               n_pages, device="cuda:0", reserve_blocks=reserve)
+    cap = w.n_in_blocks + reserve              # what the slab was sized for (it may hold a little more)
+    keep = max(cap - 64, 8)                    # live blocks after each round's eviction
+    g = np.random.default_rng(4000 + seed)
+    free_pages = list(range(w.n_pages, n_pages))[::-1]
+    earlier = [w.req_tokens[w.req_off[r]: w.req_off[r + 1]] for r in range(w.n_req)]
+    d2o = np.arange(w.n_in_blocks, dtype=np.int64)          # device block id -> oracle block id
+    tot = dict(inserted=0, evicted=0, compactions=0, forced=0)
+
+    def o2d():
+        inv = np.full(otree.n_in_blocks, -1, np.int64)
+        inv[d2o] = np.arange(len(d2o))
+        return inv
+
+    def compact():
+        nonlocal d2o
+        id_map = skv.skv_tree_compact(dtree)
+        assert len(id_map) == len(d2o)
+        live = id_map >= 0
+        assert np.array_equal(id_map[live], np.arange(live.sum()))          # dense, old order kept
+        d2o = d2o[live]
+        info = dtree.info()
+        assert info["n_in_blocks"] == len(d2o) == info["n_blocks"] == otree.n_blocks
+        tot["compactions"] += 1
+
+    def state_agrees(tag):
+        info = dtree.info()
+        assert info["n_in_blocks"] == len(d2o) and info["n_blocks"] == otree.n_blocks, tag
+        n = len(d2o)
+        hit = torch.zeros(max(n, 1), dtype=torch.int32, device="cuda:0")
+        ucnt, hit_pre, u_pre = torch.zeros_like(hit), torch.zeros_like(hit), torch.zeros_like(hit)
+        priv = torch.zeros(max(n, 1), dtype=torch.uint8, device="cuda:0")
+        skv.skv_counters_read(dtree, hit, ucnt)
+        skv.skv_block_state_read(dtree, priv, hit_pre, u_pre)
+        ep = device_epochs(skv, dtree)
+        o_hit, o_ucnt = otree.counters()
+        o_state = otree.block_state()
+        o_ep = otree.epochs()
+        alive = np.flatnonzero(priv[:n].cpu().numpy() != 255)
+        o_alive = np.flatnonzero(o_state[0] != 255)
+        assert np.array_equal(d2o[alive], o_alive), tag                      # the same blocks exist
+        sel = d2o[alive]
+        assert np.array_equal(hit[:n].cpu().numpy().view(np.uint32)[alive], o_hit[sel]), tag
+        assert np.array_equal(ucnt[:n].cpu().numpy().view(np.uint32)[alive], o_ucnt[sel]), tag
+        assert np.array_equal(priv[:n].cpu().numpy()[alive], o_state[0][sel]), tag
+        assert np.array_equal(hit_pre[:n].cpu().numpy().view(np.uint32)[alive], o_state[1][sel]), tag
+        assert np.array_equal(u_pre[:n].cpu().numpy().view(np.uint32)[alive], o_state[2][sel]), tag
+        assert np.array_equal(ep[alive], o_ep[sel]), tag
+
+    def lookups_agree(tag):
+        for t in range(w.n_tenants):
+            sample = [earlier[i] for i in g.choice(len(earlier), min(24, len(earlier)), replace=False)]
+            o = np.concatenate([[0], np.cumsum([len(x) for x in sample])]).astype(np.int32)
+            tk = np.concatenate(sample + [np.zeros(0, np.int32)]).astype(np.int32)
+            ten = np.full(len(sample), t, np.int32)
+            mb2 = max(max(len(x) // B for x in sample), 1)
+            ml2, pt2 = device_match(skv, dtree, o, tk, ten, mb2)
+            o_ml2, o_pt2 = otree.match(o, tk, ten, mb2)
+            assert np.array_equal(ml2, o_ml2) and np.array_equal(pt2, o_pt2), (seed, tag, t)
+
+    for rnd in range(n_rounds):
+        otree.set_epoch(rnd + 1)
+        skv.skv_set_epoch(dtree, rnd + 1)
+        reqs, off, toks, tenants = make_round(g, earlier, vocab, w.n_tenants, n_req, block_vocab)
+        mb = max(max(len(x) // B for x in reqs), 1)
+        mlen, pt = device_match(skv, dtree, off, toks, tenants, mb)
+        o_mlen, o_pt, o_ids = otree.match(off, toks, tenants, mb, want_ids=True)
+        assert np.array_equal(mlen, o_mlen) and np.array_equal(pt, o_pt), (seed, rnd)
+        new_pages = np.full((n_req, mb + 1), -1, np.int32)
+        for r, x in enumerate(reqs):
+            for j in range(len(x) // B - mlen[r] // B):
+                new_pages[r, j] = free_pages.pop()
+        if g.random() < 0.1:
+            compact()                                   # also when nothing forces it
+            lookups_agree((rnd, "compacted early"))
+        try:
+            first, n = skv.skv_tree_insert(dtree, off, toks, tenants, mlen, new_pages, private_copies=copies)
+        except skv.SkvError as e:
+            assert e.code == -2, e                      # the slab is full of records that evictions left behind
+            lookups_agree((rnd, "refused"))             # the refused insert changed nothing
+            compact()
+            tot["forced"] += 1
+            first, n = skv.skv_tree_insert(dtree, off, toks, tenants, mlen, new_pages, private_copies=copies)
+        o_before = otree.n_in_blocks
+        o_first, o_n = otree.insert(off, toks, tenants, mlen, new_pages, private_copies=copies)
+        assert np.array_equal(first, o_first) and np.array_equal(n, o_n), (seed, rnd)
+        # both sides number the new blocks upwards from their own count, in request order
+        d2o = np.concatenate([d2o, o_before + np.arange(int(n.sum()), dtype=np.int64)])
+        assert otree.n_in_blocks == o_before + int(n.sum())
+        tot["inserted"] += int(n.sum())
+        if rnd % 3 == 0:                                 # the verifier clears a random part of what is cached
+            alive = np.flatnonzero(otree.block_state()[0] != 255)
+            pick = alive[g.random(len(alive)) < 0.3]
+            if len(pick):
+                assert (o2d()[pick] >= 0).all()
+                skv.skv_promote(dtree, _dev(o2d()[pick].astype(np.int32)))
+                otree.promote(pick.astype(np.int32))
+        earlier = (earlier + reqs)[-200:]
+        lookups_agree(rnd)
+        protect = o_ids[o_ids >= 0][::3].astype(np.int32)
+        n_want = max(otree.n_blocks - keep, 0)
+        ids, pages = skv.skv_evict(dtree, n_want, o2d()[protect].astype(np.int32))
+        want_ids, want_pages = otree.evict(n_want, protect)
+        assert np.array_equal(d2o[ids], want_ids) and np.array_equal(pages, want_pages), (seed, rnd)
+        tot["evicted"] += len(ids)
+        free_pages += [int(p) for p in pages]
+        lookups_agree((rnd, "evicted"))
+        state_agrees((seed, rnd))
+    compact()
+    lookups_agree("end")
+    state_agrees((seed, "end"))
+    tot["cap"] = cap
+    return tot
+
+
+@pytest.mark.parametrize("copies", [False, True])
+def test_compaction_keeps_a_small_slab_going(copies):
+    """Many times the slab's capacity goes through it; every forced compaction is followed by an insert that
+    succeeds, and lookups, evictions, counters, visibility bits and epochs stay those of the oracle throughout."""
+    for seed in range(6):
+        print(f"[compact] copies={copies} stream {seed}", flush=True)
+        tot = run_compact_stream(seed, n_rounds=60, copies=copies)
+        print(f"[compact]   {tot}", flush=True)
+        assert tot["evicted"] > 3 * tot["cap"] and tot["forced"] >= 3, tot
+
+
+# ---------------------------------------------------------------------------------------------
 # per-tenant copies of the same content (Section 4.1): insert below the requester's own path, branching lookup
 
 def run_copy_stream(seed, n_rounds=5, n_req=10):
