@@ -111,14 +111,17 @@ int skv_tree_build(const skv_tree_desc* desc, void* d_slab, size_t bytes, void* 
  * input block id at the first difference).  Its search explores at most 10 such branch points per request
  * exhaustively, the 64 oldest visible copies per position and 4096 root-to-end walks; a request that runs into one
  * of these limits may be given a shorter path than the longest one, and the limit is recorded (skv_match_limits_read).
- * This mode reads the visibility bits back from the device first.
+ * The search runs on the host, against the tree as earlier requests of the same batch left it (their new blocks
+ * are visible to their tenant).  It uses the host's copy of the visibility bits, which is fetched from the device
+ * again (on `stream`) only if skv_promote or skv_window_roll has been enqueued since it was taken.
  * New entries receive the input
  * block ids n_in_blocks, n_in_blocks + 1, ... in that order, start with zeroed counters, and are visible to
  * skv_match calls enqueued afterwards.  first_inserted[r] / n_inserted[r] report the index of the request's
  * first new block and their number (pages given for blocks below first_inserted[r] stay unused).
  * Errors, nothing changed: SKV_EINVAL for null pointers, decreasing offsets, a tenant outside
  * [0, n_tenants), a page id outside [0, n_pages), already backing a cached block, or named twice;
- * SKV_ENOMEM when the slab's capacity (blocks, or child-table slots) would be exceeded.
+ * SKV_ENOMEM when the slab's capacity (blocks, or child-table slots) would be exceeded (records that evictions
+ * left behind count until skv_tree_compact reclaims them).
  * Copies the changed records to the device on `stream` and synchronises it before returning.  Must not
  * overlap with other calls on the tree. */
 int skv_tree_insert(skv_tree* tree, int32_t n_req, const int32_t* req_off, const int32_t* req_tokens,

@@ -79,6 +79,10 @@ struct SkvHostMirror {
   std::vector<int32_t> flat_of;       // [n_in_blocks]
   std::vector<uint8_t> page_used;     // [n_pages]
   int64_t live_blocks = 0;
+  // Visibility words as the host last knew them.  Kernels change them (promotion, the safeguard's demotion), so
+  // every call that enqueues such a kernel marks the copy stale and the next reader fetches it again.
+  std::vector<int32_t> vis;           // [n_blocks]
+  bool vis_stale = false;
 };
 
 namespace {
@@ -361,6 +365,7 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   }
   m->canon.assign(h_canon, h_canon + n_blocks);
   m->page.assign(h_page, h_page + n_blocks);
+  m->vis.assign(h_meta, h_meta + n_blocks);
   m->flat_of.assign(h_flat_of, h_flat_of + nib);
   m->live_blocks = n_blocks;
   m->slots.assign(slots.begin(), slots.begin() + n_slots);
@@ -465,63 +470,83 @@ struct Inserter {
     m->kids[node] = kids;
     return true;
   }
-  // ---- private copies: the requester's longest visible path, depth first, older copies first ----
-  std::vector<int32_t> vis_meta;   // visibility word of every block record (read back, then extended)
-  bool track_vis = false;
-  const int32_t* sx = nullptr;
-  int64_t snb = 0, cur_len = 0, best_len = 0;
-  int32_t stenant = 0, best_node = 0, best_used = 0;
-  bool have_best = false;
-  void consider(int32_t node, int32_t used) {
-    if (!have_best || cur_len > best_len) { best_len = cur_len; best_node = node; best_used = used; have_best = true; }
-  }
-  void descend(int32_t node, int64_t j) {
-    bool went = false;
-    const SkvNode n = m->nodes[node];
-    if (j < snb && n.tab_cap) {
-      const uint64_t h = skv_hash_block_host(sx + j * 16);
-      std::vector<std::pair<int32_t, int32_t>> cands;  // (input id of the first block, child)
-      for (uint32_t s = (uint32_t)h & (uint32_t)(n.tab_cap - 1);; s = (s + 1) & (uint32_t)(n.tab_cap - 1)) {
-        const SkvSlot& sl = m->slots[(size_t)n.tab_off + s];
-        if (sl.child == -1) break;
-        if (sl.child >= 0 && sl.hash_lo == (uint32_t)h && sl.hash_hi == (uint32_t)(h >> 32) &&
-            !memcmp(&m->tok[(size_t)m->nodes[sl.child].first * 16], sx + j * 16, 64))
-          cands.push_back({m->canon[m->nodes[sl.child].first], sl.child});
-      }
-      std::sort(cands.begin(), cands.end());
-      for (const auto& cd : cands) {
-        const SkvNode c = m->nodes[cd.second];
-        int64_t k = 0;
-        while (k < c.n_blocks && j + k < snb) {
-          if (memcmp(&m->tok[((size_t)c.first + k) * 16], sx + (j + k) * 16, 64)) break;
-          const int32_t mt = vis_meta[(size_t)c.first + k];
-          if (mt < 0 && (mt & 0x7fffffff) != stenant) break;
-          ++k;
-        }
-        if (k == 0) continue;
-        went = true;
-        cur_len += k;
-        if (k == c.n_blocks) descend(cd.second, j + k);
-        else consider(cd.second, (int32_t)k);
-        cur_len -= k;
-        if (best_len == snb) return;
-      }
+  // ---- private copies (Section 4.1): where the requester's own longest visible path ends ----
+  // Several children of a node may start with the same block (one copy per tenant that could not see the others),
+  // so the path is not unique and has to be searched: a stack of open positions, each with the copies that match
+  // the request's next block ordered by the input id of their first block (the oldest copy is tried first).  A copy
+  // is followed for as many blocks as match and are visible; if that covers the whole node the position below it
+  // is opened, otherwise the path ends inside the node.  The first end that reaches the greatest depth is kept.
+  struct PathEnd { int32_t node = 0, used = 0; int64_t depth = -1; };
+  struct OpenPos {
+    int32_t node;
+    int64_t depth;
+    std::vector<std::pair<int32_t, int32_t>> copies;  // (input id of the copy's first block, child node)
+    size_t next = 0;
+    bool extended = false;                             // some copy took the path further than this node
+  };
+  void matching_copies(int32_t node, const int32_t* blk, std::vector<std::pair<int32_t, int32_t>>& out) const {
+    const SkvNode& n = m->nodes[node];
+    if (!n.tab_cap) return;
+    const uint64_t h = skv_hash_block_host(blk);
+    const uint32_t mask = (uint32_t)(n.tab_cap - 1);
+    for (uint32_t s = (uint32_t)h & mask; m->slots[(size_t)n.tab_off + s].child != -1; s = (s + 1) & mask) {
+      const SkvSlot& sl = m->slots[(size_t)n.tab_off + s];
+      if (sl.child < 0 || sl.hash_lo != (uint32_t)h || sl.hash_hi != (uint32_t)(h >> 32)) continue;
+      const int32_t f = m->nodes[sl.child].first;
+      if (!memcmp(&m->tok[(size_t)f * 16], blk, 64)) out.push_back({m->canon[f], sl.child});
     }
-    if (!went) consider(node, n.n_blocks);
+    std::sort(out.begin(), out.end());
+  }
+  int32_t visible_run(const SkvNode& c, const int32_t* x, int64_t room, int32_t tenant) const {
+    const int64_t lim = std::min<int64_t>(c.n_blocks, room);
+    int64_t k = 0;
+    for (; k < lim; ++k) {
+      const int32_t word = m->vis[(size_t)c.first + k];
+      if (word < 0 && (word & 0x7fffffff) != tenant) break;   // private to somebody else
+      if (memcmp(&m->tok[((size_t)c.first + k) * 16], x + k * 16, 64)) break;
+    }
+    return (int32_t)k;
+  }
+  PathEnd longest_visible_path(const int32_t* x, int64_t nb, int32_t tenant) const {
+    PathEnd best;
+    std::vector<OpenPos> open;
+    auto open_at = [&](int32_t node, int64_t depth) {
+      open.push_back(OpenPos{node, depth, {}});
+      if (depth < nb) matching_copies(node, x + depth * 16, open.back().copies);
+    };
+    auto offer = [&](int32_t node, int32_t used, int64_t depth) {
+      if (depth > best.depth) best = PathEnd{node, used, depth};
+    };
+    open_at(0, 0);
+    while (!open.empty() && best.depth < nb) {
+      OpenPos& p = open.back();
+      if (p.next == p.copies.size()) {          // every copy tried: a position nothing continued is an end itself
+        if (!p.extended) offer(p.node, m->nodes[p.node].n_blocks, p.depth);
+        open.pop_back();
+        continue;
+      }
+      const int32_t child = p.copies[p.next++].second;
+      const SkvNode c = m->nodes[child];
+      const int32_t k = visible_run(c, x + p.depth * 16, nb - p.depth, tenant);
+      if (k == 0) continue;
+      p.extended = true;
+      const int64_t below = p.depth + k;        // (p may dangle after the next push)
+      if (k == c.n_blocks) open_at(child, below);
+      else offer(child, k, below);
+    }
+    return best;
   }
   // Appends blocks [k, nb) of the request below the end of its own longest visible path.  Returns k, or -1
   // when the slab is full.
   int64_t insert_copy(const int32_t* x, int64_t nb, int32_t tenant, const int32_t* pages, int64_t k_vis, int64_t* n_new) {
     *n_new = 0;
-    sx = x; snb = nb; stenant = tenant; cur_len = 0; best_len = 0; best_node = 0; best_used = 0; have_best = false;
-    descend(0, 0);
-    const int64_t k = best_len;
+    const PathEnd end = longest_visible_path(x, nb, tenant);
+    const int64_t k = end.depth;
     if (k >= nb || k < k_vis) return k;
-    int32_t at = best_node;
-    const SkvNode run = m->nodes[at];
-    if (best_used < run.n_blocks) {  // the path stops inside a compressed edge: split it there
+    const int32_t at = end.node;
+    if (end.used < m->nodes[at].n_blocks) {  // the path stops inside a compressed edge: split it there
       if ((int64_t)m->nodes.size() + 2 > m->cap_blocks + 1) return -1;
-      if (!split(at, best_used)) return -1;
+      if (!split(at, end.used)) return -1;
     }
     const int64_t add = nb - k;
     if (n_blocks + add > m->cap_blocks || n_in + add > m->cap_blocks) return -1;
@@ -564,7 +589,7 @@ struct Inserter {
     for (int64_t j = i; j < nb; ++j) {
       page.push_back(pages[j - k_vis]);
       meta.push_back((int32_t)0x80000000 | tenant);
-      if (track_vis) vis_meta.push_back((int32_t)0x80000000 | tenant);
+      m->vis.push_back((int32_t)0x80000000 | tenant);
       m->page.push_back(pages[j - k_vis]);
       m->canon.push_back((int32_t)(n_in + (j - i)));
       m->flat_of.push_back((int32_t)(n_blocks + (j - i)));
@@ -647,13 +672,12 @@ extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_of
   const size_t slots_used0 = m->slots_used, tok0 = m->tok.size(), blocks0 = m->canon.size(), in0 = m->flat_of.size();
   Inserter ins{t, m, t->dev.n_blocks, t->n_in_blocks, {}, {}, SIZE_MAX, 0, SIZE_MAX, 0};
   hipStream_t st = (hipStream_t)stream;
-  if (private_copies) {  // the requester's own path depends on the visibility bits, which live on the device
-    ins.track_vis = true;
-    ins.vis_meta.resize((size_t)t->dev.n_blocks);
-    if (t->dev.n_blocks) {
-      SKV_HIP(hipMemcpyAsync(ins.vis_meta.data(), t->dev.meta, (size_t)t->dev.n_blocks * 4, hipMemcpyDeviceToHost, st));
-      SKV_HIP(hipStreamSynchronize(st));
-    }
+  // The requester's own path depends on the visibility bits.  The host's copy of them is exact unless a
+  // promotion or a safeguard window has been enqueued since it was taken; only then is it fetched again.
+  if (private_copies && m->vis_stale && t->dev.n_blocks) {
+    SKV_HIP(hipMemcpyAsync(m->vis.data(), t->dev.meta, (size_t)t->dev.n_blocks * 4, hipMemcpyDeviceToHost, st));
+    SKV_HIP(hipStreamSynchronize(st));
+    m->vis_stale = false;
   }
   bool full = false;
   for (int32_t r = 0; r < n_req && !full; ++r) {
@@ -673,7 +697,7 @@ extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_of
     m->nodes = nodes0; m->kids = kids0; m->slots = slots0; m->page_used = used0;
     m->filled = filled0; m->parent = parent0;
     m->slots_used = slots_used0; m->tok.resize(tok0);
-    m->canon.resize(blocks0); m->page.resize(blocks0); m->flat_of.resize(in0);
+    m->canon.resize(blocks0); m->page.resize(blocks0); m->vis.resize(blocks0); m->flat_of.resize(in0);
     return SKV_ENOMEM;
   }
   // upload: the appended block records, then the spans of node and slot records that changed
@@ -912,6 +936,8 @@ extern "C" int skv_tree_compact(skv_tree* t, int32_t* id_map, int64_t* n_in_bloc
   m->canon = std::move(canon);
   m->page = std::move(page);
   m->flat_of = std::move(flat_of);
+  m->vis = std::move(n_meta);   // just read back: exact
+  m->vis_stale = false;
   t->dev.n_blocks = (int32_t)nb;
   t->dev.n_nodes = (int32_t)m->nodes.size() - 1;
   t->n_in_blocks = n_ids;
@@ -960,6 +986,7 @@ extern "C" int skv_window_roll(skv_tree* t, const skv_rdr_policy* pol, int32_t* 
   if (d_n_demoted) fill_u32_kernel<<<1, 64, 0, st>>>((uint32_t*)d_n_demoted, 1, 0u);
   if (t->dev.n_blocks)
     window_roll_kernel<<<grid_for((size_t)t->dev.n_blocks, 256), 256, 0, st>>>(t->dev, *pol, d_n_demoted);
+  if (t->host) t->host->vis_stale = true;   // the kernel decides the demotions
   SKV_HIP(hipGetLastError());
   return SKV_OK;
 }
@@ -967,6 +994,7 @@ extern "C" int skv_window_roll(skv_tree* t, const skv_rdr_policy* pol, int32_t* 
 extern "C" int skv_promote(skv_tree* t, const int32_t* d_block_ids, int32_t n, void* stream) {
   if (!t || n < 0 || (n > 0 && !d_block_ids)) return SKV_EINVAL;
   if (n) promote_kernel<<<grid_for((size_t)n, 256), 256, 0, (hipStream_t)stream>>>(t->dev, t->n_in_blocks, d_block_ids, n);
+  if (n && t->host) t->host->vis_stale = true;   // the ids are in device memory: the host has not seen them
   SKV_HIP(hipGetLastError());
   return SKV_OK;
 }

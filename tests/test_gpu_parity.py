@@ -835,7 +835,8 @@ def run_compact_stream(seed, n_rounds, copies, reserve=96, n_req=10):
     free_pages = list(range(w.n_pages, n_pages))[::-1]
     earlier = [w.req_tokens[w.req_off[r]: w.req_off[r + 1]] for r in range(w.n_req)]
     d2o = np.arange(w.n_in_blocks, dtype=np.int64)          # device block id -> oracle block id
-    tot = dict(inserted=0, evicted=0, compactions=0, forced=0)
+    tot = dict(inserted=0, evicted=0, compactions=0, forced=0, demoted=0)
+    roll_policy = dict(direction=0, tau=(1, 2), min_hits=1, n_consec=1, u_pre_max=1)
 
     def o2d():
         inv = np.full(otree.n_in_blocks, -1, np.int64)
@@ -927,6 +928,13 @@ def run_compact_stream(seed, n_rounds, copies, reserve=96, n_req=10):
                 otree.promote(pick.astype(np.int32))
         earlier = (earlier + reqs)[-200:]
         lookups_agree(rnd)
+        if rnd % 5 == 4:                                 # a safeguard window ends: some public blocks turn private
+            n_dem = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+            skv.skv_window_roll(dtree, skv.rdr_policy(**roll_policy), n_dem)
+            want = otree.window_roll(**roll_policy)
+            assert int(n_dem.item()) == want, (seed, rnd)
+            tot["demoted"] += want
+            lookups_agree((rnd, "window"))
         protect = o_ids[o_ids >= 0][::3].astype(np.int32)
         n_want = max(otree.n_blocks - keep, 0)
         ids, pages = skv.skv_evict(dtree, n_want, o2d()[protect].astype(np.int32))
@@ -947,11 +955,14 @@ def run_compact_stream(seed, n_rounds, copies, reserve=96, n_req=10):
 def test_compaction_keeps_a_small_slab_going(copies):
     """Many times the slab's capacity goes through it; every forced compaction is followed by an insert that
     succeeds, and lookups, evictions, counters, visibility bits and epochs stay those of the oracle throughout."""
+    demoted = 0
     for seed in range(6):
         print(f"[compact] copies={copies} stream {seed}", flush=True)
         tot = run_compact_stream(seed, n_rounds=60, copies=copies)
         print(f"[compact]   {tot}", flush=True)
         assert tot["evicted"] > 3 * tot["cap"] and tot["forced"] >= 3, tot
+        demoted += tot["demoted"]
+    assert demoted > 0
 
 
 # ---------------------------------------------------------------------------------------------
