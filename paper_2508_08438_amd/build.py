@@ -8,7 +8,7 @@ INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB_PATH = os.path.join(_HERE, "libskv.so")
 SOURCES = ["skv_tree.hip", "skv_match.hip", "skv_gather.hip", "skv_attn.hip", "skv_decode.hip"]
 # packed fp32 instructions are switched off for every device translation unit
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared", "-Wall", "-fno-honor-nans",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
