@@ -303,6 +303,30 @@ def main():
     copy_gbs = 2.0 * n_copy / (ce[0].elapsed_time(ce[1]) * 1e-3 / 5) / 1e9
     del src, dst
 
+    # what the matrix cores sustain on operands distributed like this workload's tensors, and on constants: the
+    # clock under matrix load depends on the values, so the first is the ceiling the attention kernel can be held to
+    mfma_rate = None
+    if w.attn.dtype == "bf16":
+        n_val = skv.MFMA_RATE_OPERAND_BYTES // 2
+        chunk = np.random.default_rng(7).standard_normal(1 << 20).astype(np.float32)
+        if not args.hard:
+            chunk /= np.sqrt(w.attn.head_dim)
+        h_ops = torch.from_numpy(chunk).to(torch.bfloat16).repeat((n_val >> 20) + 1)[:n_val]
+        sink = torch.empty(skv.MFMA_RATE_SINK_BYTES // 4, dtype=torch.float32).to(sess.device)
+        mfma_rate = {"kernel": "mfma_rate_kernel", "unit": "TFLOP/s", "instruction": "v_mfma_f32_32x32x16_bf16"}
+        for label, ops in (("workload_like_values", h_ops.to(sess.device)),
+                           ("constant_values", torch.ones(n_val, dtype=torch.bfloat16).to(sess.device))):
+            skv.skv_mfma_rate(ops, 40000, sink)            # the clock settles under load first
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            ev[0].record()
+            for i in range(3):
+                fl = skv.skv_mfma_rate(ops, 40000, sink)
+                ev[i + 1].record()
+            torch.cuda.synchronize()
+            ts = [ev[i].elapsed_time(ev[i + 1]) * 1e-3 for i in range(3)]
+            mfma_rate[label] = fl / float(np.median(ts)) / 1e12
+        del h_ops, sink, ops
+
     tokens = float(len(w.req_tokens))
     a = w.attn
     flops = main_fig["attention_tflops"] * 1e12 * t_attn
@@ -340,6 +364,10 @@ def main():
                      "flops_per_launch": flops, "avg_launch_ms": t_attn * 1e3},
         "hbm_traffic_per_launch": traffic_rec,
     }
+    if mfma_rate:
+        out["mfma_sustained"] = mfma_rate
+        out["roofline"]["frac_of_sustained_mfma_rate_on_workload_like_values"] = (
+            main_fig["attention_tflops"] / mfma_rate["workload_like_values"])
 
     # the counters after one step of this batch: what the safeguard would read (reuse statistics of the workload)
     hit, ucnt = sess.counters()

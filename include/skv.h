@@ -287,6 +287,21 @@ int skv_scatter_kv(const skv_attn_desc* desc, int32_t n_req, const void* d_knew,
  * Errors: SKV_EINVAL for null or misaligned pointers or a size that is not a multiple of 16. */
 int skv_stream_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
 
+/* Measurement aid for the attention roofline (Section 2.1 attention; Section 6 reports prefill time): the rate at
+ * which the chip sustains the bf16 matrix instruction of skv_prefill_attn (32x32x16, fp32 accumulate) on operand
+ * values of the caller's choosing, with nothing else running -- operands stay in registers, one workgroup of eight
+ * wavefronts per compute unit, `iters` rounds of 16 instructions each.  The clock under matrix load depends on the operand values,
+ * so the rate for values distributed like a workload's K/V/Q is the ceiling that workload's attention can be held
+ * against; constants give the nominal peak.  d_operands: DEVICE, at least SKV_MFMA_RATE_OPERAND_BYTES bytes of
+ * bf16 values, 16-byte aligned (read once); d_sink: DEVICE, at least SKV_MFMA_RATE_SINK_BYTES bytes (overwritten,
+ * keeps the results alive).  *flops (HOST, may be NULL) receives the floating-point operations one call issues;
+ * the caller times the call on `stream`.
+ * Errors: SKV_EINVAL for null or misaligned pointers or iters < 1; SKV_ENOMEM for buffers that are too small. */
+#define SKV_MFMA_RATE_OPERAND_BYTES ((size_t)512 * 512 * 6 * 32)
+#define SKV_MFMA_RATE_SINK_BYTES ((size_t)512 * 512 * 4)
+int skv_mfma_rate(const void* d_operands, size_t operand_bytes, int32_t iters, float* d_sink, size_t sink_bytes,
+                  double* flops, void* stream);
+
 /* Bytes of device workspace skv_prefill_attn needs for n_req requests and at most
  * total_q_rows uncached tokens in the batch (the work list of the bf16 kernel and one page of zeros that
  * stands in for key groups without data); the call overwrites it. */

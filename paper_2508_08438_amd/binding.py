@@ -18,7 +18,7 @@ SKV_F32, SKV_BF16 = 0, 1
 SKV_OK, SKV_EINVAL, SKV_ENOMEM, SKV_ERANGE, SKV_EHIP = 0, -1, -2, -3, -4
 SKV_LIMIT_BRANCH_POINTS, SKV_LIMIT_COPIES, SKV_LIMIT_WALKS = 1, 2, 4
 
-EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_size_for_capacity", "skv_tree_build", "skv_tree_insert", "skv_set_epoch", "skv_block_epochs_read", "skv_evict", "skv_tree_compact",
+EXPORTS = ["skv_strerror", "skv_last_hip_error", "skv_tree_build_size", "skv_tree_size_for_capacity", "skv_tree_build", "skv_tree_insert", "skv_set_epoch", "skv_block_epochs_read", "skv_evict", "skv_tree_compact", "skv_mfma_rate",
            "skv_tree_info", "skv_tree_destroy", "skv_match", "skv_match_limits_read", "skv_counters_read",
            "skv_counters_reset", "skv_window_roll", "skv_promote", "skv_block_state_read", "skv_suffix_offsets", "skv_gather_kv",
            "skv_scatter_kv", "skv_stream_copy", "skv_decode_attn_workspace_size", "skv_decode_attn",
@@ -91,6 +91,7 @@ def lib():
                                               i32, vp, vp]
         l.skv_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
         l.skv_tree_compact.argtypes = [vp, vp, C.POINTER(i64), vp]
+        l.skv_mfma_rate.argtypes = [vp, C.c_size_t, i32, vp, C.c_size_t, C.POINTER(C.c_double), vp]
         l.skv_match_limits_read.argtypes = [vp, C.POINTER(C.c_uint32), i32, vp]
         _lib = l
     return _lib
@@ -213,6 +214,18 @@ def skv_evict(tree: Tree, n_want: int, protect_ids=(), stream=None):
         _check(lib().skv_evict(tree.handle, n_want, hp(prot), len(prot), hp(ids), hp(pages), C.byref(k),
                                _stream(stream)), "skv_evict")
     return ids[: k.value], pages[: k.value]
+
+
+MFMA_RATE_OPERAND_BYTES = 512 * 512 * 6 * 32
+MFMA_RATE_SINK_BYTES = 512 * 512 * 4
+
+
+def skv_mfma_rate(operands: torch.Tensor, iters: int, sink: torch.Tensor, stream=None) -> float:
+    """Enqueues the matrix-rate kernel; returns the floating-point operations it issues."""
+    flops = C.c_double()
+    _check(lib().skv_mfma_rate(_dptr(operands), operands.numel() * operands.element_size(), iters, _dptr(sink),
+                               sink.numel() * sink.element_size(), C.byref(flops), _stream(stream)), "skv_mfma_rate")
+    return flops.value
 
 
 def skv_tree_compact(tree: Tree, stream=None):

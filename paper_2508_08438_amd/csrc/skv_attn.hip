@@ -848,3 +848,57 @@ extern "C" int skv_prefill_attn_static(const skv_attn_desc* desc, int32_t n_req,
   return prefill_attn_enqueue(desc, n_req, d_q, d_knew, d_vnew, d_q_off, total_q_rows, d_kpool, d_vpool, n_pages,
                               d_matched_len, d_page_table, max_blocks, d_out, ws, stream);
 }
+
+// ---- measurement aid: what the matrix cores sustain on given operand values ----
+// The clock the chip holds under matrix load depends on the values flowing through the multipliers, so the rate a
+// kernel can reach is a property of its data as well as of its code.  Every wavefront keeps six (A, B) operand
+// pairs of the caller's data in registers and issues the attention kernel's MFMA back to back into four
+// accumulators: no memory traffic, no other instructions.  One workgroup of eight wavefronts per compute unit; its
+// LDS claim keeps a second workgroup off the unit, so every SIMD runs exactly two wavefronts from start to end.
+namespace {
+constexpr int kRateMaxBlocks = 512, kRateThreads = 512, kRatePairs = 6, kRateLdsBytes = 96 * 1024;
+__global__ __launch_bounds__(kRateThreads) void mfma_rate_kernel(const u32x4* __restrict__ ops, float* __restrict__ sink,
+                                                                 int iters) {
+  __shared__ uint32_t claim[kRateLdsBytes / 4];
+  const size_t lane_id = (size_t)blockIdx.x * kRateThreads + threadIdx.x;
+  bf16x8 a[kRatePairs], b[kRatePairs];
+#pragma unroll
+  for (int i = 0; i < kRatePairs; ++i) {
+    const u32x4 x = ops[(lane_id * kRatePairs + i) * 2], y = ops[(lane_id * kRatePairs + i) * 2 + 1];
+    a[i] = __builtin_bit_cast(bf16x8, x);
+    b[i] = __builtin_bit_cast(bf16x8, y);
+  }
+  f32x16 c[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) c[j][e] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      c[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j % kRatePairs], b[(j / 4 + j) % kRatePairs], c[j & 3], 0, 0, 0);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) t += c[j][e];
+  volatile uint32_t* used = claim;             // the array has to be used to be allocated
+  used[threadIdx.x] = __float_as_uint(t);
+  sink[lane_id] = __uint_as_float(used[threadIdx.x]);
+}
+}  // namespace
+
+extern "C" int skv_mfma_rate(const void* d_operands, size_t operand_bytes, int32_t iters, float* d_sink,
+                             size_t sink_bytes, double* flops, void* stream) {
+  if (!d_operands || !d_sink || iters < 1 || ((uintptr_t)d_operands & 15)) return SKV_EINVAL;
+  if (operand_bytes < SKV_MFMA_RATE_OPERAND_BYTES || sink_bytes < SKV_MFMA_RATE_SINK_BYTES) return SKV_ENOMEM;
+  int dev = 0, cus = 0;
+  SKV_HIP(hipGetDevice(&dev));
+  SKV_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  const int blocks = cus < kRateMaxBlocks ? cus : kRateMaxBlocks;
+  mfma_rate_kernel<<<blocks, kRateThreads, 0, (hipStream_t)stream>>>((const u32x4*)d_operands, d_sink, iters);
+  SKV_HIP(hipGetLastError());
+  if (flops) *flops = (double)blocks * (kRateThreads / 64) * (double)iters * 16.0 * (2.0 * 32 * 32 * 16);
+  return SKV_OK;
+}
