@@ -277,18 +277,24 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   // or the page of zeros when the group has no data (past the end of the sequence, or a page id outside the pool).
   // A tile's bases are read with lane broadcasts.  Two consecutive windows are held; K tiles run one tile ahead of
   // V tiles, so for one iteration in sixteen K reads the later window while V still reads the earlier one.
-  auto fetch_window = [&](int w, uint64_t& ak, uint64_t& av) __attribute__((always_inline)) {
+  // A window is fetched in two parts, so that the page-table read can be in flight while other work goes on: the
+  // page id first, the addresses from it later.
+  auto window_page = [&](int w) __attribute__((always_inline)) {
+    const int gi = w * 64 + lane;
+    int page = -1;
+    if (gi * SKV_BLOCK_TOKENS < L && gi < p.max_blocks)
+      page = __builtin_nontemporal_load(&p.page_table[(size_t)r * p.max_blocks + gi]);
+    return page;
+  };
+  auto window_bases = [&](int w, int page, uint64_t& ak, uint64_t& av) __attribute__((always_inline)) {
     const int gi = w * 64 + lane;
     const int key0 = gi * SKV_BLOCK_TOKENS;
     uint64_t k = (uint64_t)p.zero_page, v = k;
     if (key0 < L) {
-      if (gi < p.max_blocks) {
-        const int page = p.page_table[(size_t)r * p.max_blocks + gi];
-        if (page >= 0 && page < p.n_pages) {
-          const uint64_t off = ((uint64_t)page * SKV_BLOCK_TOKENS * p.Hkv + kvh) * (kD * 2);
-          k = (uint64_t)p.kpool + off;
-          v = (uint64_t)p.vpool + off;
-        }
+      if (page >= 0 && page < p.n_pages) {
+        const uint64_t off = ((uint64_t)page * SKV_BLOCK_TOKENS * p.Hkv + kvh) * (kD * 2);
+        k = (uint64_t)p.kpool + off;
+        v = (uint64_t)p.vpool + off;
       }
     } else if (key0 < Ltot) {
       const uint64_t off = ((uint64_t)(qbase + key0 - L) * p.Hkv + kvh) * (kD * 2);
@@ -297,6 +303,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
     }
     ak = k;
     av = v;
+  };
+  auto fetch_window = [&](int w, uint64_t& ak, uint64_t& av) __attribute__((always_inline)) {
+    window_bases(w, window_page(w), ak, av);
   };
   auto lane_bcast = [&](uint64_t x, int idx) __attribute__((always_inline)) {
     const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)x, idx);
@@ -331,6 +340,44 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   };
   auto load_v_tile = [&](int t, int stage_idx) __attribute__((always_inline)) {
     load_half_tile((t >> 4) == win ? av_cur : av_nxt, t, Vs + stage_idx * kTile);
+  };
+  // Inside the main loop the same loads are split in two: the segment bases of the tiles an iteration will request
+  // (K two tiles ahead, V one) are broadcast out of the windows during the iteration before, between its half-steps,
+  // so that the iteration itself starts with nothing but the four load instructions.  Right after a barrier every
+  // wave of the workgroup is at this point at once, and what stands here keeps all matrix cores waiting.
+  typedef const __attribute__((address_space(1))) char* gptr;
+  gptr nk[2], nv[2];
+  int pend_page = -1;
+  bool pend = false;
+  auto prep_bases = [&](int kt_next) __attribute__((always_inline)) {
+    if (((kt_next + 1) >> 4) != win) {   // V enters the next window: move on and ask for the page ids of the one
+      ++win;                             // after it; K needs that window fourteen iterations from now, the iteration
+      ak_cur = ak_nxt;                   // after this one turns the ids into addresses, behind its barrier, where
+      av_cur = av_nxt;                   // every load of this wave has landed anyway
+      pend_page = window_page(win + 1);
+      pend = true;
+    }
+    const int tk = kt_next + 2, tv = kt_next + 1;
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) {
+      const int g = (wave >> 2) + 2 * cc;
+      nk[cc] = lane_bcast((tk >> 4) == win ? ak_cur : ak_nxt, ((tk & 15) << 2) + g);
+      nv[cc] = lane_bcast((tv >> 4) == win ? av_cur : av_nxt, ((tv & 15) << 2) + g);
+    }
+  };
+  auto issue_half_tile = [&]<bool kWhole>(const gptr (&b)[2], int t, __bf16* dst_stage) __attribute__((always_inline)) {
+    const int key_base = t * kBN;
+    __bf16* const dst = dst_stage + wave * kSeg;
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) {
+      unsigned off = t_off;
+      if (!kWhole && key_base + kBN > Ltot) {   // as in load_half_tile
+        const int n_valid = Ltot - (key_base + ((wave >> 2) + 2 * cc) * 16);
+        if (n_valid > 0 && n_valid < 16) off = (unsigned)min(t_row, n_valid - 1) * row_bytes + t_col;
+      }
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b[cc] + off),
+                                       (lds_void*)(dst + cc * 8 * kSeg), 16, 0, 0);
+    }
   };
   // a wave's direct loads are in LDS once its vector-memory counter has drained; the barrier then publishes them
   auto tile_barrier = [&]() __attribute__((always_inline)) {
@@ -541,29 +588,30 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   auto iteration = [&]<bool kFast>(int kt) __attribute__((always_inline)) {
     const int st1 = st0 == 2 ? 0 : st0 + 1;    // stage of tile kt + 1
     const int st2 = st1 == 2 ? 0 : st1 + 1;    // stage of tiles kt + 2 and kt - 1
-    if (((kt + 1) >> 4) != win) {   // V enters the next window: move on, fetch the one after it
-      ++win;
-      ak_cur = ak_nxt;
-      av_cur = av_nxt;
-      fetch_window(win + 1, ak_nxt, av_nxt);
+    if (__builtin_expect(pend, 0)) {
+      window_bases(win + 1, pend_page, ak_nxt, av_nxt);
+      pend = false;
     }
-    if (kFast || kt + 2 < n_tiles) load_k_tile(kt + 2, st2);
-    if (kFast || kt + 1 < n_tiles) load_v_tile(kt + 1, st1);
+    if (kFast || kt + 2 < n_tiles) issue_half_tile.template operator()<kFast>(nk, kt + 2, Ks + st2 * kTile);
+    if (kFast || kt + 1 < n_tiles) issue_half_tile.template operator()<kFast>(nv, kt + 1, Vs + st1 * kTile);
     const uint32_t kb0 = k_base + st0 * kStageBytes;   // K(kt)
     const uint32_t kb1 = k_base + st1 * kStageBytes;   // K(kt + 1)
     const uint32_t vbp = v_base + st2 * kStageBytes;   // V(kt - 1)
     const uint32_t vb0 = v_base + st0 * kStageBytes;   // V(kt)
     if (kFast) {
       half_step_fast(kb0 + kHalfBytes, kb1, vbp + kHalfBytes, vb0, s[1], s[0], pb[1], pb[0]);
+      prep_bases(kt + 1);
       half_step_fast(kb1, kb1 + kHalfBytes, vb0, vb0 + kHalfBytes, s[0], s[1], pb[0], pb[1]);
     } else {
       half_step_slow(2 * kt, kb0 + kHalfBytes, kb1, vbp + kHalfBytes, vb0, s[1], s[0], pb[1], pb[0]);
+      prep_bases(kt + 1);
       half_step_slow(2 * kt + 1, kb1, kb1 + kHalfBytes, vb0, vb0 + kHalfBytes, s[0], s[1], pb[0], pb[1]);
     }
     tile_barrier();
     st0 = st1;
   };
   int kt = 0;
+  prep_bases(0);
   iteration.template operator()<false>(kt++);
   for (; kt < kt_fast; ++kt) iteration.template operator()<true>(kt);
   for (; kt <= n_tiles; ++kt) iteration.template operator()<false>(kt);
