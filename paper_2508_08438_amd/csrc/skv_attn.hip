@@ -494,19 +494,45 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   auto half_step_fast = [&](uint32_t kb, uint32_t kb_next, uint32_t vb, uint32_t vb_next, f32x16& dst, f32x16& cur,
                             bf16x8 (&p_use)[2], bf16x8 (&p_make)[2]) __attribute__((always_inline)) {
     ssum[0] = ssum[1] = 0.f;
+    // One exponential behind every MFMA, never two in a row: the transcendental unit takes about four issue slots
+    // per instruction but works beside the issue port, so a second one right behind the first would hold the
+    // wavefront until the unit is free again.  The pair is packed and summed one step later, behind the next
+    // exponential.
+    float e0 = 0.f, e1 = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      float e0, e1;
       lds_wait(11, kfr[i & 3]);
       dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[i & 3], qf[i], i == 0 ? zero16 : dst, 0, 0, 0);
       kfr[i & 3] = i < 4 ? k_frag(kb, i + 4) : k_frag(kb_next, i - 4);
-      exp_pair(cur, i, p_make, e0, e1, 0);
+      const float f0 = __builtin_amdgcn_exp2f(cur[2 * i] - m_ref);
+      if (i > 0) {
+        f32x2 pr = {e0, e1};
+        const bf16x2 cv = __builtin_convertvector(pr, bf16x2);
+        pk[2 * ((i - 1) & 3)] = cv[0];
+        pk[2 * ((i - 1) & 3) + 1] = cv[1];
+        ssum[0] += e0;
+      }
       __builtin_amdgcn_sched_barrier(0);
       lds_wait(10, vfr[i & 3]);
       o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[i & 3], p_use[i >> 2], o[i & 3], 0, 0, 0);
       vfr[i & 3] = i < 4 ? v_frag(vb, i + 4) : v_frag(vb_next, i - 4);
-      exp_pair(cur, i, p_make, e0, e1, 1);
+      const float f1 = __builtin_amdgcn_exp2f(cur[2 * i + 1] - m_ref);
+      if (i > 0) {
+        ssum[1] += e1;
+        if (((i - 1) & 3) == 3) p_make[(i - 1) >> 2] = pk;
+      }
+      e0 = f0;
+      e1 = f1;
       __builtin_amdgcn_sched_barrier(0);
+    }
+    {
+      f32x2 pr = {e0, e1};
+      const bf16x2 cv = __builtin_convertvector(pr, bf16x2);
+      pk[6] = cv[0];
+      pk[7] = cv[1];
+      ssum[0] += e0;
+      ssum[1] += e1;
+      p_make[1] = pk;
     }
     if (__builtin_expect(__any(!(ssum[0] + ssum[1] <= kSumLimit)), 0)) move_reference(cur, p_make);
     l_run += ssum[0] + ssum[1];
