@@ -600,6 +600,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
       kfr[ks & 3] = ks < 4 ? k_frag(k_base, ks + 4) : k_frag(k_base + kHalfBytes, ks - 4);
       __builtin_amdgcn_sched_barrier(0);
     }
+    // (idle states for the last MFMA: the compiler's wait-state insertion does not look through the branch inside
+    // mask(), and the row maximum behind it would read score registers the matrix core has not written yet)
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+v"(s[0]));
     mask(s[0], 0);
     m_ref = row_max(s[0]);   // finite: key 0 is visible to every query
   }

@@ -164,6 +164,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attn_kernel(DecParams p) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
       s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)(kb + ks * 32), qf[ks], s, 0, 0, 0);
+    // The scores are read by vector instructions right behind a branch (the ragged-tile test below).  The compiler's
+    // wait-state insertion does not look through that branch, and without the states an MFMA result needs before a
+    // vector instruction may read it the row maxima are taken from registers the matrix core has not written yet
+    // (seen as run-to-run differences in the last bits).  Twelve idle states cover the four-pass MFMA.
+    asm volatile("s_nop 7\n\ts_nop 3" : "+v"(s));
     const int key0 = kt * kBN + 16 * wave + 4 * g4;
     if (kt * kBN + kBN > ctx) {
 #pragma unroll

@@ -181,3 +181,21 @@ def test_limits_read_and_stream_copy_argument_checks(skv):
     assert l.skv_stream_copy(None, fake, 64, None) == -1
     assert l.skv_stream_copy(fake, fake, 24, None) == -1               # not a multiple of 16
     assert l.skv_stream_copy(C.c_void_p((1 << 20) + 4), fake, 64, None) == -1
+
+
+def test_no_reader_of_an_mfma_result_sits_right_behind_a_branch():
+    """Compiles the two MFMA kernels to assembly and scans them (see mfma_hazard_scan): 12 idle states cover the
+    8-pass 32x32x16 and the 4-pass 16x16x32 instructions the kernels use."""
+    import os, subprocess, tempfile
+    from mfma_hazard_scan import scan
+    from paper_2508_08438_amd import build
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in build.FLAGS if f not in ("-shared", "-fPIC")]
+    for src, kernel in (("skv_attn.hip", "attn_bf16_kernel"), ("skv_decode.hip", "decode_attn_kernel")):
+        with tempfile.TemporaryDirectory() as tmp:
+            out = os.path.join(tmp, "k.s")
+            r = subprocess.run([hipcc, *flags, "--cuda-device-only", "-S", "-I", build.INCLUDE, "-I", build.CSRC, "-o", out,
+                                os.path.join(build.CSRC, src)], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+            assert r.returncode == 0, r.stdout
+            found = scan(open(out).read(), kernel)
+        assert not found, (kernel, found)
