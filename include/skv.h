@@ -92,7 +92,7 @@ int skv_tree_build(const skv_tree_desc* desc, void* d_slab, size_t bytes, void* 
                    skv_tree** out);
 
 /* Insert after a prefill (Section 4.3.1 Insert: new KV blocks are appended along the request's path;
- * Section 4.1 and Section 5: every new block starts private, with the requester as creator_id).  All arrays are HOST
+ * Section 4.1 and Section 6: every new block starts private, with the requester as creator_id).  All arrays are HOST
  * arrays.  For request r (tokens req_tokens[req_off[r] .. req_off[r+1]), tenant req_tenant[r]) the full
  * 16-token blocks that the tree does not hold yet are appended below the point where the request's token
  * path leaves the tree (splitting a compressed node when that point lies inside it), private to the tenant.

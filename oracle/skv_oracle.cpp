@@ -30,7 +30,7 @@
 //    and which direction is "right" is parity unpinned.  The mechanics for a given parameter set are
 //    pinned against an independent recomputation from the counters.
 //
-//  * Insert after prefill (Section 4.3.1 Insert, Section 4.1 and Section 5: new blocks start private), promotion as a flag
+//  * Insert after prefill (Section 4.3.1 Insert, Section 4.1 and Section 6: new blocks start private), promotion as a flag
 //    flip (Section 4.2.3), per-tenant copies of the same content with a depth-first longest-visible-path search
 //    (Section 4.1), access epochs and block-by-block eviction of the oldest unprotected childless tail
 //    (Section 4.3.1 Evict, Section 4.3.2 progressive eviction), and the byte copy of new KV blocks into pool
@@ -325,7 +325,7 @@ int64_t existing_prefix_blocks(Tree* t, const int32_t* tok, int64_t n_blocks) {
   return j;
 }
 
-// Insert after a prefill (Section 4.3.1 Insert; Section 4.1 and Section 5: every new block starts private): the full
+// Insert after a prefill (Section 4.3.1 Insert; Section 4.1 and Section 6: every new block starts private): the full
 // blocks of request r that the tree does not hold yet are appended along its path with private_tag = 1 and
 // creator_id = the request's tenant.  One copy per block-prefix: blocks whose tokens are already on the path
 // keep their entry, whoever created it.  new_pages[r][j] is the page of the request's block

@@ -412,7 +412,7 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   return SKV_OK;
 }
 
-// ---- insertion after prefill (Section 4.3.1 Insert; Section 4.1 and Section 5: new blocks are private by default) ----
+// ---- insertion after prefill (Section 4.3.1 Insert; Section 4.1 and Section 6: new blocks are private by default) ----
 namespace {
 
 struct Inserter {
