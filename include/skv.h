@@ -111,22 +111,29 @@ int skv_tree_build(const skv_tree_desc* desc, void* d_slab, size_t bytes, void* 
  * input block id at the first difference).  Its search explores at most 10 such branch points per request
  * exhaustively, the 64 oldest visible copies per position and 4096 root-to-end walks; a request that runs into one
  * of these limits may be given a shorter path than the longest one, and the limit is recorded (skv_match_limits_read).
- * The search runs on the host, against the tree as earlier requests of the same batch left it (their new blocks
- * are visible to their tenant).  It uses the host's copy of the visibility bits, which is fetched from the device
- * again (on `stream`) only if skv_promote or skv_window_roll has been enqueued since it was taken.
+ * path_end (HOST, n_req entries, may be NULL; used with private_copies only): the path ends skv_match wrote for
+ * this batch (copied to the host by the caller), taken on the tree and the visibility bits as they are when the
+ * insert is called.  The lookup has then already found each requester's longest visible path, and the insert only
+ * continues it through blocks that earlier requests of the same batch added for the same tenant (nothing else can
+ * have become visible to that tenant in between) -- no search and no visibility bits are needed.  matched_len[r]
+ * must be the matched length of the same lookup.  Without path_end the insert searches itself, on the host, against
+ * the tree as earlier requests of the batch left it; it then uses the host's copy of the visibility bits, which is
+ * fetched from the device again (on `stream`) only if skv_promote or skv_window_roll has been enqueued since it
+ * was taken.
  * New entries receive the input
  * block ids n_in_blocks, n_in_blocks + 1, ... in that order, start with zeroed counters, and are visible to
  * skv_match calls enqueued afterwards.  first_inserted[r] / n_inserted[r] report the index of the request's
  * first new block and their number (pages given for blocks below first_inserted[r] stay unused).
  * Errors, nothing changed: SKV_EINVAL for null pointers, decreasing offsets, a tenant outside
- * [0, n_tenants), a page id outside [0, n_pages), already backing a cached block, or named twice;
+ * [0, n_tenants), a page id outside [0, n_pages), already backing a cached block, or named twice, or a path end
+ * that does not fit the request (no such record, an evicted one, or not the request's block matched_len/16 - 1);
  * SKV_ENOMEM when the slab's capacity (blocks, or child-table slots) would be exceeded (records that evictions
  * left behind count until skv_tree_compact reclaims them).
  * Copies the changed records to the device on `stream` and synchronises it before returning.  Must not
  * overlap with other calls on the tree. */
 int skv_tree_insert(skv_tree* tree, int32_t n_req, const int32_t* req_off, const int32_t* req_tokens,
                     const int32_t* req_tenant, const int32_t* matched_len, const int32_t* new_pages,
-                    int32_t max_new_blocks, int32_t private_copies, int32_t* first_inserted,
+                    int32_t max_new_blocks, int32_t private_copies, const int32_t* path_end, int32_t* first_inserted,
                     int32_t* n_inserted, void* stream);
 
 /* Global epoch counter (Section 4.3.2: the index keeps a global epoch_counter and every entry its most
@@ -185,10 +192,14 @@ void skv_tree_destroy(skv_tree* tree);
  * tenant may see and the longest path wins, as described at skv_tree_insert; only that path's blocks are
  * counted and stamped.
  * A request whose tenant is outside [0, n_tenants) or whose offsets decrease matches nothing.
+ * d_path_end (DEVICE, n_req entries, may be NULL) receives where each request's path ends inside the index: the
+ * record number of its last matched block, -1 if nothing matched.  The number is meaningful only to
+ * skv_tree_insert, which can then append a request's new blocks below that point without looking the path up
+ * again; it stays valid until the next skv_evict or skv_tree_compact.
  * Errors: SKV_EINVAL for null pointers or negative sizes.  n_req == 0 is a no-op. */
 int skv_match(skv_tree* tree, int32_t n_req, const int32_t* d_req_off, const int32_t* d_req_tokens,
               const int32_t* d_req_tenant, int32_t max_blocks, int32_t* d_matched_len,
-              int32_t* d_page_table, void* stream);
+              int32_t* d_page_table, int32_t* d_path_end, void* stream);
 
 /* Limits of the branching lookup (trees with per-tenant copies, Section 4.1): which of them any request has run
  * into since the tree was built or the word was last cleared -- SKV_LIMIT_BRANCH_POINTS (more than 10 positions

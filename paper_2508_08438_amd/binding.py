@@ -68,7 +68,7 @@ def lib():
         l.skv_tree_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
         l.skv_tree_destroy.argtypes = [vp]
         l.skv_tree_destroy.restype = None
-        l.skv_match.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, vp]
+        l.skv_match.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, vp, vp]
         l.skv_counters_read.argtypes = [vp, vp, vp, vp]
         l.skv_counters_reset.argtypes = [vp, vp]
         l.skv_window_roll.argtypes = [vp, C.POINTER(RdrPolicy), vp, vp]
@@ -80,7 +80,7 @@ def lib():
         l.skv_block_epochs_read.argtypes = [vp, vp, vp]
         l.skv_evict.argtypes = [vp, C.c_int64, vp, C.c_int64, vp, vp, C.POINTER(C.c_int64), vp]
         l.skv_tree_size_for_capacity.argtypes = [C.c_int64, C.POINTER(C.c_size_t)]
-        l.skv_tree_insert.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
+        l.skv_tree_insert.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
         l.skv_scatter_kv.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, vp, vp, i32, vp, vp, i32, vp]
         l.skv_suffix_offsets.argtypes = [i32, vp, vp, vp, vp]
         l.skv_gather_kv.argtypes = [C.POINTER(AttnDesc), i32, vp, vp, i32, vp, vp, i32, vp, vp, vp, i64, vp]
@@ -179,8 +179,9 @@ def skv_tree_build(seq_tokens, seq_off, blk_sensitive, blk_owner, blk_page, n_te
 
 
 def skv_tree_insert(tree: Tree, req_off, req_tokens, req_tenant, matched_len, new_pages, private_copies=False,
-                    stream=None):
-    """Host arrays in (numpy int32), per-request (first_inserted, n_inserted) out."""
+                    stream=None, path_end=None):
+    """Host arrays in (numpy int32), per-request (first_inserted, n_inserted) out.  path_end: the lookup's path ends
+    for this batch (host copy), copies mode only."""
     a = [np.ascontiguousarray(x, dtype=np.int32) for x in (req_off, req_tokens, req_tenant, matched_len, new_pages)]
     n_req = len(a[2])
     assert len(a[0]) == n_req + 1 and len(a[3]) == n_req and a[4].ndim == 2 and a[4].shape[0] == n_req
@@ -188,8 +189,11 @@ def skv_tree_insert(tree: Tree, req_off, req_tokens, req_tenant, matched_len, ne
     n = np.zeros(n_req, dtype=np.int32)
     hp = lambda x: C.c_void_p(x.ctypes.data) if x.size else None
     with torch.cuda.device(tree.slab.device):
+        pe = None if path_end is None else np.ascontiguousarray(path_end, dtype=np.int32)
+        assert pe is None or len(pe) == n_req
         _check(lib().skv_tree_insert(tree.handle, n_req, hp(a[0]), hp(a[1]), hp(a[2]), hp(a[3]), hp(a[4]),
-                                     a[4].shape[1], int(private_copies), hp(first), hp(n), _stream(stream)),
+                                     a[4].shape[1], int(private_copies), None if pe is None else C.c_void_p(pe.ctypes.data),
+                                     hp(first), hp(n), _stream(stream)),
                "skv_tree_insert")
     return first, n
 
@@ -239,14 +243,17 @@ def skv_tree_compact(tree: Tree, stream=None):
     return id_map[:n]
 
 
-def skv_match(tree: Tree, req_off, req_tokens, req_tenant, max_blocks, matched_len, page_table, stream=None):
+def skv_match(tree: Tree, req_off, req_tokens, req_tenant, max_blocks, matched_len, page_table, stream=None,
+              path_end=None):
     n_req = req_tenant.numel()
+    assert path_end is None or (path_end.dtype == torch.int32 and path_end.numel() >= n_req)
     assert req_off.dtype == req_tokens.dtype == req_tenant.dtype == torch.int32
     assert matched_len.dtype == page_table.dtype == torch.int32
     assert req_off.numel() == n_req + 1 and matched_len.numel() >= n_req
     assert page_table.numel() >= n_req * max_blocks
     _check(lib().skv_match(tree.handle, n_req, _dptr(req_off), _dptr(req_tokens), _dptr(req_tenant),
-                           max_blocks, _dptr(matched_len), _dptr(page_table), _stream(stream)), "skv_match")
+                           max_blocks, _dptr(matched_len), _dptr(page_table),
+                           _dptr(path_end) if path_end is not None else None, _stream(stream)), "skv_match")
 
 
 def skv_match_limits_read(tree: Tree, clear=True, stream=None) -> int:

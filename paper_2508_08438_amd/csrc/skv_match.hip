@@ -86,7 +86,7 @@ template <int kCoop>
 __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
     SkvTreeDev t, int n_req, const int32_t* __restrict__ req_off, const int32_t* __restrict__ req_tok,
     const int32_t* __restrict__ req_tenant, int max_blocks, int32_t* __restrict__ matched_len,
-    int32_t* __restrict__ page_table) {
+    int32_t* __restrict__ page_table, int32_t* __restrict__ path_end) {
   __shared__ int stop_at[2][kWavesPerWg];   // per round parity and wavefront: blocks of the node matched before its stop
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = kCoop > 1 ? uniform(threadIdx.x >> 6) : 0;   // wavefront within the request's team
@@ -106,6 +106,7 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
 
   int j = 0;      // blocks matched so far
   int node = 0;   // current node (root)
+  int last = -1;  // record of the last matched block: where the path ends
   int parity = 0;
   bool stop = false;
   while (j < nb && !stop) {
@@ -203,11 +204,15 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
         }
       }
       j = jn + upto;
+      if (upto > 0) last = first + upto - 1;
       if (ended) stop = true;
     }
     node = child;
   }
-  if (wave == 0 && lane == 0) matched_len[r] = j * SKV_BLOCK_TOKENS;
+  if (wave == 0 && lane == 0) {
+    matched_len[r] = j * SKV_BLOCK_TOKENS;
+    if (path_end) path_end[r] = last;
+  }
   for (int i = j + wave * kWave + lane; i < max_blocks; i += kWave * kCoop) row[i] = -1;
 }
 
@@ -282,7 +287,7 @@ __device__ inline int find_child_ranked(const SkvTreeDev& t, const SkvNode nd, c
 __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_copies_kernel(
     SkvTreeDev t, int n_req, const int32_t* __restrict__ req_off, const int32_t* __restrict__ req_tok,
     const int32_t* __restrict__ req_tenant, int max_blocks, int32_t* __restrict__ matched_len,
-    int32_t* __restrict__ page_table) {
+    int32_t* __restrict__ page_table, int32_t* __restrict__ path_end) {
   const int lane = threadIdx.x & (kWave - 1);
   const int r = blockIdx.x * kWavesPerWg + (threadIdx.x >> 6);
   if (r >= n_req) return;
@@ -379,6 +384,7 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_copies_kernel(
   __threadfence();   // row[] was written by other lanes of this wavefront: make the stores visible to the loads below
   const uint32_t tbit = 1u << (tenant & 31);
   const int tword = 1 + (tenant >> 5);
+  const int last = best > 0 ? uniform(row[best - 1]) : -1;   // record of the last block on the chosen path
   for (int i = lane; i < best; i += kWave) {
     const int blk = row[i];
     row[i] = t.page[blk];
@@ -388,6 +394,7 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_copies_kernel(
     t.epoch[blk] = t.cur_epoch;
   }
   if (lane == 0) matched_len[r] = best * SKV_BLOCK_TOKENS;
+  if (lane == 0 && path_end) path_end[r] = last;
   if (lane == 0 && limits) atomicOr(t.limits, limits);
   for (int i = best + lane; i < max_blocks; i += kWave) row[i] = -1;
 }
@@ -426,7 +433,7 @@ __global__ void skv_suffix_offsets_kernel(int n_req, const int32_t* __restrict__
 
 extern "C" int skv_match(skv_tree* t, int32_t n_req, const int32_t* d_req_off,
                          const int32_t* d_req_tokens, const int32_t* d_req_tenant, int32_t max_blocks,
-                         int32_t* d_matched_len, int32_t* d_page_table, void* stream) {
+                         int32_t* d_matched_len, int32_t* d_page_table, int32_t* d_path_end, void* stream) {
   if (!t || n_req < 0 || max_blocks < 0) return SKV_EINVAL;
   if (n_req == 0) return SKV_OK;
   if (!d_req_off || !d_req_tokens || !d_req_tenant || !d_matched_len) return SKV_EINVAL;
@@ -434,13 +441,13 @@ extern "C" int skv_match(skv_tree* t, int32_t n_req, const int32_t* d_req_off,
   const int grid = (n_req + kWavesPerWg - 1) / kWavesPerWg;
   if (t->has_copies)
     skv_match_copies_kernel<<<grid, kWave * kWavesPerWg, 0, (hipStream_t)stream>>>(
-        t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table);
+        t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table, d_path_end);
   else if (n_req <= kCoopMaxRequests)   // few requests: a workgroup each
     skv_match_kernel<kWavesPerWg><<<n_req, kWave * kWavesPerWg, 0, (hipStream_t)stream>>>(
-        t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table);
+        t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table, d_path_end);
   else
     skv_match_kernel<1><<<grid, kWave * kWavesPerWg, 0, (hipStream_t)stream>>>(
-        t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table);
+        t->dev, n_req, d_req_off, d_req_tokens, d_req_tenant, max_blocks, d_matched_len, d_page_table, d_path_end);
   SKV_HIP(hipGetLastError());
   return SKV_OK;
 }

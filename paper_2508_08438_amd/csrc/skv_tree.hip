@@ -77,6 +77,7 @@ struct SkvHostMirror {
   std::vector<int32_t> tok;           // [n_blocks][16], flat order
   std::vector<int32_t> canon, page;   // [n_blocks] input block id (-1 once evicted), page id
   std::vector<int32_t> flat_of;       // [n_in_blocks]
+  std::vector<int32_t> node_of;       // [n_blocks] node that holds each block record (path ends name records)
   std::vector<uint8_t> page_used;     // [n_pages]
   int64_t live_blocks = 0;
   // Visibility words as the host last knew them.  Kernels change them (promotion, the safeguard's demotion), so
@@ -366,6 +367,9 @@ extern "C" int skv_tree_build(const skv_tree_desc* d, void* d_slab, size_t bytes
   m->canon.assign(h_canon, h_canon + n_blocks);
   m->page.assign(h_page, h_page + n_blocks);
   m->vis.assign(h_meta, h_meta + n_blocks);
+  m->node_of.assign((size_t)n_blocks, 0);
+  for (int32_t n = 1; n <= n_nodes; ++n)
+    for (int32_t k = 0; k < nodes[n].n_blocks; ++k) m->node_of[(size_t)nodes[n].first + k] = n;
   m->flat_of.assign(h_flat_of, h_flat_of + nib);
   m->live_blocks = n_blocks;
   m->slots.assign(slots.begin(), slots.begin() + n_slots);
@@ -553,6 +557,56 @@ struct Inserter {
     if ((int64_t)m->nodes.size() + 1 > m->cap_blocks + 1) return -1;
     return append(at, x, k, nb, tenant, pages, k_vis, n_new) ? k : -1;
   }
+  // The same with the end of the requester's path given (the record of its last matched block, -1 for none; found by
+  // the lookup before this batch).  What the lookup could not see are the blocks earlier requests of this batch added
+  // for the same tenant; they hang below path ends the lookup did see, so the path is continued through them and
+  // nothing else: a child (or the rest of a node) counts only if its blocks were created in this batch (records from
+  // nb0 on) by this tenant.  Returns the index of the first new block, or -1 when the slab is full.
+  int64_t insert_below(const int32_t* x, int64_t nb, int32_t tenant, const int32_t* pages, int64_t k_vis,
+                       int32_t end_rec, int64_t nb0, int64_t* n_new) {
+    *n_new = 0;
+    int32_t node = 0, used = 0;
+    if (end_rec >= 0) {
+      node = m->node_of[end_rec];
+      used = end_rec - m->nodes[node].first + 1;
+    }
+    int64_t k = k_vis;
+    auto mine = [&](int32_t rec) { return rec >= nb0 && m->vis[rec] == ((int32_t)0x80000000 | tenant); };
+    while (k < nb) {
+      const SkvNode nd = m->nodes[node];
+      if (used < nd.n_blocks) {              // inside a node: only this batch's own blocks continue the path
+        const int32_t rec = nd.first + used;
+        if (!mine(rec) || memcmp(&m->tok[(size_t)rec * 16], x + k * 16, 64)) break;
+        ++used;
+        ++k;
+        continue;
+      }
+      int32_t next = -1;
+      if (nd.tab_cap) {
+        const uint64_t h = skv_hash_block_host(x + k * 16);
+        const uint32_t mask = (uint32_t)(nd.tab_cap - 1);
+        for (uint32_t q = (uint32_t)h & mask; m->slots[(size_t)nd.tab_off + q].child != -1; q = (q + 1) & mask) {
+          const SkvSlot& sl = m->slots[(size_t)nd.tab_off + q];
+          if (sl.child < 0 || sl.hash_lo != (uint32_t)h || sl.hash_hi != (uint32_t)(h >> 32)) continue;
+          const int32_t rec = m->nodes[sl.child].first;
+          if (mine(rec) && !memcmp(&m->tok[(size_t)rec * 16], x + k * 16, 64)) { next = sl.child; break; }
+        }
+      }
+      if (next < 0) break;
+      node = next;
+      used = 1;
+      ++k;
+    }
+    if (k >= nb) return k;
+    if (used < m->nodes[node].n_blocks) {    // the path stops inside a compressed edge: split it there
+      if ((int64_t)m->nodes.size() + 2 > m->cap_blocks + 1) return -1;
+      if (!split(node, used)) return -1;
+    }
+    const int64_t add = nb - k;
+    if (n_blocks + add > m->cap_blocks || n_in + add > m->cap_blocks) return -1;
+    if ((int64_t)m->nodes.size() + 1 > m->cap_blocks + 1) return -1;
+    return append(node, x, k, nb, tenant, pages, k_vis, n_new) ? k : -1;
+  }
   // Cuts node c after its first j blocks: a new node takes the rest together with the child table.
   bool split(int32_t c, int64_t j) {
     const SkvNode run = m->nodes[c];
@@ -565,6 +619,7 @@ struct Inserter {
       const int32_t gc = m->slots[(size_t)run.tab_off + q].child;
       if (gc >= 0) m->parent[gc] = tail;
     }
+    for (int32_t k = (int32_t)j; k < run.n_blocks; ++k) m->node_of[(size_t)run.first + k] = tail;
     m->nodes[c].n_blocks = (int32_t)j;
     m->nodes[c].tab_off = 0;
     m->nodes[c].tab_cap = 0;
@@ -590,6 +645,7 @@ struct Inserter {
       page.push_back(pages[j - k_vis]);
       meta.push_back((int32_t)0x80000000 | tenant);
       m->vis.push_back((int32_t)0x80000000 | tenant);
+      m->node_of.push_back(fresh);
       m->page.push_back(pages[j - k_vis]);
       m->canon.push_back((int32_t)(n_in + (j - i)));
       m->flat_of.push_back((int32_t)(n_blocks + (j - i)));
@@ -638,8 +694,8 @@ struct Inserter {
 
 extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_off, const int32_t* req_tokens,
                                const int32_t* req_tenant, const int32_t* matched_len, const int32_t* new_pages,
-                               int32_t max_new_blocks, int32_t private_copies, int32_t* first_inserted,
-                               int32_t* n_inserted, void* stream) {
+                               int32_t max_new_blocks, int32_t private_copies, const int32_t* path_end,
+                               int32_t* first_inserted, int32_t* n_inserted, void* stream) {
   if (!t || !t->host || n_req < 0 || max_new_blocks < 0) return SKV_EINVAL;
   if (n_req == 0) return SKV_OK;
   if (!req_off || !req_tenant || !matched_len || !first_inserted || !n_inserted) return SKV_EINVAL;
@@ -661,6 +717,15 @@ extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_of
         seen[pg] = 1;
       }
       have[r] = h;
+      if (private_copies && path_end) {   // the record must be this request's last matched block
+        const int64_t k_vis = matched_len[r] / SKV_BLOCK_TOKENS;
+        const int32_t e = path_end[r];
+        if (k_vis == 0 ? e != -1
+                       : (e < 0 || e >= t->dev.n_blocks || m->canon[e] < 0 ||
+                          k_vis * SKV_BLOCK_TOKENS > req_off[r + 1] - req_off[r] ||
+                          memcmp(&m->tok[(size_t)e * 16], req_tokens + req_off[r] + (k_vis - 1) * 16, 64)))
+          return SKV_EINVAL;
+      }
     }
   }
   // work on the mirror; a full slab restores the snapshot and changes nothing
@@ -668,13 +733,13 @@ extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_of
   const std::vector<int32_t> kids0 = m->kids;
   const std::vector<SkvSlot> slots0 = m->slots;
   const std::vector<uint8_t> used0 = m->page_used;
-  const std::vector<int32_t> filled0 = m->filled, parent0 = m->parent;
+  const std::vector<int32_t> filled0 = m->filled, parent0 = m->parent, node_of0 = m->node_of;
   const size_t slots_used0 = m->slots_used, tok0 = m->tok.size(), blocks0 = m->canon.size(), in0 = m->flat_of.size();
   Inserter ins{t, m, t->dev.n_blocks, t->n_in_blocks, {}, {}, SIZE_MAX, 0, SIZE_MAX, 0};
   hipStream_t st = (hipStream_t)stream;
   // The requester's own path depends on the visibility bits.  The host's copy of them is exact unless a
   // promotion or a safeguard window has been enqueued since it was taken; only then is it fetched again.
-  if (private_copies && m->vis_stale && t->dev.n_blocks) {
+  if (private_copies && !path_end && m->vis_stale && t->dev.n_blocks) {
     SKV_HIP(hipMemcpyAsync(m->vis.data(), t->dev.meta, (size_t)t->dev.n_blocks * 4, hipMemcpyDeviceToHost, st));
     SKV_HIP(hipStreamSynchronize(st));
     m->vis_stale = false;
@@ -686,16 +751,17 @@ extern "C" int skv_tree_insert(skv_tree* t, int32_t n_req, const int32_t* req_of
     if (nb > k_vis + have[r]) nb = k_vis + have[r];
     int64_t n_new = 0;
     const int32_t* pages_r = new_pages + (size_t)r * max_new_blocks;
-    const int64_t first = private_copies
-                              ? ins.insert_copy(req_tokens + req_off[r], nb, req_tenant[r], pages_r, k_vis, &n_new)
-                              : ins.insert(req_tokens + req_off[r], nb, req_tenant[r], pages_r, k_vis, &n_new);
+    const int32_t* x = req_tokens + req_off[r];
+    const int64_t first = !private_copies ? ins.insert(x, nb, req_tenant[r], pages_r, k_vis, &n_new)
+                          : path_end      ? ins.insert_below(x, nb, req_tenant[r], pages_r, k_vis, path_end[r], t->dev.n_blocks, &n_new)
+                                          : ins.insert_copy(x, nb, req_tenant[r], pages_r, k_vis, &n_new);
     if (first < 0) { full = true; break; }
     first_inserted[r] = (int32_t)first;
     n_inserted[r] = (int32_t)n_new;
   }
   if (full) {
     m->nodes = nodes0; m->kids = kids0; m->slots = slots0; m->page_used = used0;
-    m->filled = filled0; m->parent = parent0;
+    m->filled = filled0; m->parent = parent0; m->node_of = node_of0;
     m->slots_used = slots_used0; m->tok.resize(tok0);
     m->canon.resize(blocks0); m->page.resize(blocks0); m->vis.resize(blocks0); m->flat_of.resize(in0);
     return SKV_ENOMEM;
@@ -937,6 +1003,9 @@ extern "C" int skv_tree_compact(skv_tree* t, int32_t* id_map, int64_t* n_in_bloc
   m->page = std::move(page);
   m->flat_of = std::move(flat_of);
   m->vis = std::move(n_meta);   // just read back: exact
+  m->node_of.assign((size_t)nb, 0);
+  for (size_t n = 1; n < m->nodes.size(); ++n)
+    for (int32_t k = 0; k < m->nodes[n].n_blocks; ++k) m->node_of[(size_t)m->nodes[n].first + k] = (int32_t)n;
   m->vis_stale = false;
   t->dev.n_blocks = (int32_t)nb;
   t->dev.n_nodes = (int32_t)m->nodes.size() - 1;

@@ -99,7 +99,7 @@ def test_attention_and_gather_argument_checks(skv):
     assert l.skv_prefill_attn(C.byref(good), 4, *args) == -1          # null tensors
     assert l.skv_prefill_attn(C.byref(good), 0, *args) == 0           # empty batch: nothing to do
     assert l.skv_gather_kv(C.byref(good), 4, None, None, 8, None, None, 4, None, None, None, 0, None) == -1
-    assert l.skv_match(None, 1, None, None, None, 1, None, None, None) == -1
+    assert l.skv_match(None, 1, None, None, None, 1, None, None, None, None) == -1
     assert l.skv_counters_reset(None, None) == -1
     assert l.skv_suffix_offsets(2, None, None, None, None) == -1
 
@@ -123,7 +123,7 @@ def test_insert_evict_scatter_decode_argument_checks(skv):
     n = C.c_size_t()
     k = C.c_int64()
     # tree-side calls need a tree handle
-    assert l.skv_tree_insert(None, 1, None, None, None, None, None, 0, 0, None, None, None) == -1
+    assert l.skv_tree_insert(None, 1, None, None, None, None, None, 0, 0, None, None, None, None) == -1
     assert l.skv_evict(None, 1, None, 0, None, None, C.byref(k), None) == -1
     assert l.skv_promote(None, None, 0, None) == -1
     assert l.skv_set_epoch(None, 3) == -1

@@ -546,13 +546,16 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
 
 
-def device_match(skv, tree, off, toks, tenants, mb):
+def device_match(skv, tree, off, toks, tenants, mb, want_path_end=False):
     R = len(tenants)
     mlen = torch.zeros(max(R, 1), dtype=torch.int32, device="cuda:0")
     pt = torch.full((max(R, 1), mb), -1, dtype=torch.int32, device="cuda:0")
+    pe = torch.full((max(R, 1),), -7, dtype=torch.int32, device="cuda:0") if want_path_end else None
     skv.skv_match(tree, _dev(off), _dev(toks) if len(toks) else torch.zeros(1, dtype=torch.int32, device="cuda:0"),
-                  _dev(tenants), mb, mlen, pt)
+                  _dev(tenants), mb, mlen, pt, path_end=pe)
     torch.cuda.synchronize()
+    if want_path_end:
+        return mlen[:R].cpu().numpy(), pt[:R].cpu().numpy(), pe[:R].cpu().numpy()
     return mlen[:R].cpu().numpy(), pt[:R].cpu().numpy()
 
 
@@ -652,7 +655,30 @@ def test_insert_errors_leave_the_tree_unchanged():
         with pytest.raises(skv.SkvError) as e:
             skv.skv_tree_insert(dtree, off, x, bad_ten, np.zeros(1, np.int32), bad_pages)
         assert e.value.code == skv.SKV_EINVAL
+    # path ends that do not belong to the request: a record although nothing matched, no record although something
+    # did, a record number outside the index, and the record of some other block
     mb = max(w.max_blocks, 1)
+    r_hit = int(np.argmax(np.diff(w.req_off) // B > 0))
+    one_off = np.array([0, w.req_off[r_hit + 1] - w.req_off[r_hit]], np.int32)
+    one_tok = w.req_tokens[w.req_off[r_hit]: w.req_off[r_hit + 1]]
+    one_ten = w.req_tenant[r_hit: r_hit + 1]
+    ml1, _, pe1 = device_match(skv, dtree, one_off, one_tok, one_ten, mb, want_path_end=True)
+    otree.match(one_off, one_tok, one_ten, mb)
+    if ml1[0] >= B:
+        n_rec = dtree.info()["n_blocks"]
+        wrong = [np.array([-1], np.int32), np.array([n_rec + 3], np.int32)]
+        other = [f for f in range(n_rec) if f != pe1[0]]
+        if other:
+            wrong.append(np.array([other[-1]], np.int32))
+        for bad_pe in wrong:
+            with pytest.raises(skv.SkvError) as e:
+                skv.skv_tree_insert(dtree, one_off, one_tok, one_ten, ml1, np.array([[w.n_pages]], np.int32),
+                                    private_copies=True, path_end=bad_pe)
+            assert e.value.code == skv.SKV_EINVAL
+    with pytest.raises(skv.SkvError) as e:
+        skv.skv_tree_insert(dtree, off, x, ten, np.zeros(1, np.int32), np.array([[w.n_pages]], np.int32),
+                            private_copies=True, path_end=np.array([0], np.int32))
+    assert e.value.code == skv.SKV_EINVAL
     mlen, pt = device_match(skv, dtree, w.req_off, w.req_tokens, w.req_tenant, mb)
     o_mlen, o_pt = otree.match(w.req_off, w.req_tokens, w.req_tenant, mb)
     assert np.array_equal(mlen, o_mlen) and np.array_equal(pt, o_pt)
@@ -894,18 +920,21 @@ def run_compact_stream(seed, n_rounds, copies, reserve=96, n_req=10):
         skv.skv_set_epoch(dtree, rnd + 1)
         reqs, off, toks, tenants = make_round(g, earlier, vocab, w.n_tenants, n_req, block_vocab)
         mb = max(max(len(x) // B for x in reqs), 1)
-        mlen, pt = device_match(skv, dtree, off, toks, tenants, mb)
+        mlen, pt, pe = device_match(skv, dtree, off, toks, tenants, mb, want_path_end=True)
         o_mlen, o_pt, o_ids = otree.match(off, toks, tenants, mb, want_ids=True)
         assert np.array_equal(mlen, o_mlen) and np.array_equal(pt, o_pt), (seed, rnd)
         new_pages = np.full((n_req, mb + 1), -1, np.int32)
         for r, x in enumerate(reqs):
             for j in range(len(x) // B - mlen[r] // B):
                 new_pages[r, j] = free_pages.pop()
+        use_path_ends = copies and seed % 2 == 0         # path ends name records: a compaction invalidates them
         if g.random() < 0.1:
             compact()                                   # also when nothing forces it
             lookups_agree((rnd, "compacted early"))
+            use_path_ends = False
         try:
-            first, n = skv.skv_tree_insert(dtree, off, toks, tenants, mlen, new_pages, private_copies=copies)
+            first, n = skv.skv_tree_insert(dtree, off, toks, tenants, mlen, new_pages, private_copies=copies,
+                                           path_end=pe if use_path_ends else None)
         except skv.SkvError as e:
             assert e.code == -2, e                      # the slab is full of records that evictions left behind
             lookups_agree((rnd, "refused"))             # the refused insert changed nothing
@@ -998,14 +1027,17 @@ def run_copy_stream(seed, n_rounds=5, n_req=10):
         skv.skv_set_epoch(dtree, rnd + 1)
         reqs, off, toks, tenants = make_round(g, earlier, vocab, w.n_tenants, n_req, block_vocab)
         mb = max(max(len(x) // B for x in reqs), 1)
-        mlen, pt = device_match(skv, dtree, off, toks, tenants, mb)
+        # even seeds hand the lookup's path ends to the insert (no search on the host), odd seeds let it search
+        mlen, pt, pe = device_match(skv, dtree, off, toks, tenants, mb, want_path_end=True)
         o_mlen, o_pt, o_ids = otree.match(off, toks, tenants, mb, want_ids=True)
         assert np.array_equal(mlen, o_mlen) and np.array_equal(pt, o_pt), (seed, rnd)
+        assert np.array_equal(pe >= 0, mlen > 0), (seed, rnd)
         new_pages = np.full((n_req, mb + 1), -1, np.int32)
         for r, x in enumerate(reqs):
             for j in range(len(x) // B - mlen[r] // B):
                 new_pages[r, j] = free_pages.pop()
-        first, n = skv.skv_tree_insert(dtree, off, toks, tenants, mlen, new_pages, private_copies=True)
+        first, n = skv.skv_tree_insert(dtree, off, toks, tenants, mlen, new_pages, private_copies=True,
+                                       path_end=pe if seed % 2 == 0 else None)
         o_first, o_n = otree.insert(off, toks, tenants, mlen, new_pages, private_copies=True)
         assert np.array_equal(first, o_first) and np.array_equal(n, o_n), (seed, rnd)
         inserted += int(n.sum())
@@ -1066,6 +1098,48 @@ def test_private_copy_lookup_backtracks():
     otree.match(off, req, t1, 2)
     assert ml[0] == 2 * B and list(pt[0]) == [20, 21]
     compare_state(skv, dtree, otree, "backtrack")
+
+
+def test_path_ends_continue_through_blocks_added_in_the_same_batch():
+    """The insert is given the lookup's path ends.  Requests of one batch: A adds six blocks below a shared public
+    prefix; B (same tenant) repeats A and goes on; C (same tenant) leaves A's new blocks after two of them; D (other
+    tenant) has A's content and must get its own copy; E (same tenant as A) repeats B entirely.  First new block,
+    counts and every later lookup must be the oracle's, which searches the updated tree for every request."""
+    skv = _skv()
+    g = np.random.default_rng(77)
+    blk = lambda n: g.integers(0, 30000, n * B).astype(np.int32)
+    prefix, a_new, b_more, c_other = blk(3), blk(6), blk(2), blk(3)
+    seq_off = np.array([0, len(prefix)], np.int32)
+    n_pages = 3 + 64
+    otree = oracle.OracleTree(prefix, seq_off, np.zeros(3, np.uint8), np.zeros(3, np.int32), np.arange(3, dtype=np.int32))
+    dtree = skv.skv_tree_build(prefix, seq_off, np.zeros(3, np.uint8), np.zeros(3, np.int32), np.arange(3, dtype=np.int32),
+                               3, n_pages, device="cuda:0", reserve_blocks=64)
+    reqs = [np.concatenate([prefix, a_new]), np.concatenate([prefix, a_new, b_more]),
+            np.concatenate([prefix, a_new[: 2 * B], c_other]), np.concatenate([prefix, a_new]),
+            np.concatenate([prefix, a_new, b_more])]
+    tenants = np.array([1, 1, 1, 2, 1], np.int32)
+    off = np.concatenate([[0], np.cumsum([len(x) for x in reqs])]).astype(np.int32)
+    toks = np.concatenate(reqs).astype(np.int32)
+    mb = max(len(x) // B for x in reqs)
+    mlen, pt, pe = device_match(skv, dtree, off, toks, tenants, mb, want_path_end=True)
+    o_mlen, o_pt = otree.match(off, toks, tenants, mb)
+    assert np.array_equal(mlen, o_mlen) and np.array_equal(pt, o_pt) and (mlen == 3 * B).all()
+    new_pages = np.full((len(reqs), mb), -1, np.int32)
+    nxt = 3
+    for r, x in enumerate(reqs):
+        k = len(x) // B - 3
+        new_pages[r, :k] = np.arange(nxt, nxt + k)
+        nxt += k
+    first, n = skv.skv_tree_insert(dtree, off, toks, tenants, mlen, new_pages, private_copies=True, path_end=pe)
+    o_first, o_n = otree.insert(off, toks, tenants, mlen, new_pages, private_copies=True)
+    assert np.array_equal(first, o_first) and np.array_equal(n, o_n), (first, o_first, n, o_n)
+    assert list(first) == [3, 9, 5, 3, 11] and list(n) == [6, 2, 3, 6, 0]
+    for t in range(3):
+        ten = np.full(len(reqs), t, np.int32)
+        ml2, pt2 = device_match(skv, dtree, off, toks, ten, mb)
+        o_ml2, o_pt2 = otree.match(off, toks, ten, mb)
+        assert np.array_equal(ml2, o_ml2) and np.array_equal(pt2, o_pt2), t
+    compare_state(skv, dtree, otree, "same batch")
 
 
 def test_branching_lookup_reports_its_limits():
@@ -1147,13 +1221,16 @@ def test_private_copies_config3_full_size():
     dtree = skv.skv_tree_build(w.seq_tokens, w.seq_off, w.blk_sensitive, w.blk_owner, w.blk_page, w.n_tenants,
                                w.n_pages + nb_req, device="cuda:0", reserve_blocks=nb_req)
     mb = max(w.max_blocks, 1)
-    mlen, pt = device_match(skv, dtree, w.req_off, w.req_tokens, w.req_tenant, mb)
+    mlen, pt, pe = device_match(skv, dtree, w.req_off, w.req_tokens, w.req_tenant, mb, want_path_end=True)
     o_mlen, _ = otree.match(w.req_off, w.req_tokens, w.req_tenant, mb)
     assert np.array_equal(mlen, o_mlen)
     full = np.diff(w.req_off) // B - mlen // B
     new_pages = np.full((w.n_req, int(full.max())), -1, np.int32)
     new_pages[np.arange(new_pages.shape[1])[None, :] < full[:, None]] = w.n_pages + np.arange(int(full.sum()), dtype=np.int32)
-    first, n = skv.skv_tree_insert(dtree, w.req_off, w.req_tokens, w.req_tenant, mlen, new_pages, private_copies=True)
+    # the lookup's path ends go to the insert: 256 requests of 64 tenants, many of them continuing what an earlier
+    # request of the same tenant added in this very batch
+    first, n = skv.skv_tree_insert(dtree, w.req_off, w.req_tokens, w.req_tenant, mlen, new_pages, private_copies=True,
+                                   path_end=pe)
     o_first, o_n = otree.insert(w.req_off, w.req_tokens, w.req_tenant, mlen, new_pages, private_copies=True)
     assert np.array_equal(first, o_first) and np.array_equal(n, o_n)
     print(f"[copies] c3: {int(n.sum())} of {int(full.sum())} suffix blocks inserted", flush=True)
