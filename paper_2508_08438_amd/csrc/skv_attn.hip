@@ -223,20 +223,59 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   const int n_tiles = (L + row1 + kBN - 1) / kBN;                             // 64-key tiles the workgroup streams
   const int wave_key_end = pos0 < row1 ? L + min(row1, pos0 + kRowsPerWave) : 0;  // this wave needs keys [0, wave_key_end)
 
+  // ---- the first global reads, all in flight together: the page ids of the first two address windows (what the K/V
+  // loads need first), then this wave's Q rows.  The K/V loads are issued as soon as the page ids are there; Q is
+  // staged while they travel.
+  // A window is fetched in two parts, so that the page-table read can be in flight while other work goes on: the
+  // page id first, the addresses from it later.
+  auto window_page = [&](int w) __attribute__((always_inline)) {
+    const int gi = w * 64 + lane;
+    int page = -1;
+    if (gi * SKV_BLOCK_TOKENS < L && gi < p.max_blocks)
+      page = __builtin_nontemporal_load(&p.page_table[(size_t)r * p.max_blocks + gi]);
+    return page;
+  };
+  // (the five base addresses as values: selecting between the fields of the argument block itself makes the
+  // compiler select their addresses and load through them, a vector-memory read that everything behind it waits for)
+  const uint64_t kpool_a = (uint64_t)p.kpool, vpool_a = (uint64_t)p.vpool, knew_a = (uint64_t)p.knew,
+                 vnew_a = (uint64_t)p.vnew, zero_a = (uint64_t)p.zero_page;
+  auto window_bases = [&](int w, int page, uint64_t& ak, uint64_t& av) __attribute__((always_inline)) {
+    const int gi = w * 64 + lane;
+    const int key0 = gi * SKV_BLOCK_TOKENS;
+    uint64_t k = zero_a, v = zero_a;
+    if (key0 < L) {
+      if (page >= 0 && page < p.n_pages) {
+        const uint64_t off = ((uint64_t)page * SKV_BLOCK_TOKENS * p.Hkv + kvh) * (kD * 2);
+        k = kpool_a + off;
+        v = vpool_a + off;
+      }
+    } else if (key0 < Ltot) {
+      const uint64_t off = ((uint64_t)(qbase + key0 - L) * p.Hkv + kvh) * (kD * 2);
+      k = knew_a + off;
+      v = vnew_a + off;
+    }
+    ak = k;
+    av = v;
+  };
+  const int page_w0 = window_page(0), page_w1 = window_page(1);
+
   // ---- Q fragments (B operand of S^T = K Q^T): lane holds query l32, d = 16 ks + 8 half .. +7
   // Rows are fetched whole (16 lanes x 16 B per row), multiplied once by scale * log2(e) -- the scores then leave
   // the matrix core in the units of exp2 -- and picked up from the wave's staging tile.
   const float c = p.scale * kLog2e;
   bf16x8 qf[8];
+  u32x4 qv[8];
   {
     const int c16 = lane & 15;
-    u32x4 qv[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int rr = (lane >> 4) + 4 * i;
       const int row = min(pos0 + rr, S - 1);   // rows past the tile or the request are computed and dropped
       qv[i] = *(const u32x4*)((const __bf16*)p.q + ((size_t)(qbase + row) * p.Hq + head) * kD + c16 * 8);
     }
+  }
+  auto stage_q = [&]() __attribute__((always_inline)) {
+    const int c16 = lane & 15;
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {   // the staging tile takes 16 rows at a time
 #pragma unroll
@@ -257,7 +296,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
         for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8*)(stage + rr * kD + (((2 * ks + half) ^ rr) << 3));
       }
     }
-  }
+  };
 
   f32x16 o[4];   // O^T accumulators: d = 32 a + 8(e/4) + 4 half + e%4, query = l32
 #pragma unroll
@@ -277,36 +316,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   // or the page of zeros when the group has no data (past the end of the sequence, or a page id outside the pool).
   // A tile's bases are read with lane broadcasts.  Two consecutive windows are held; K tiles run one tile ahead of
   // V tiles, so for one iteration in sixteen K reads the later window while V still reads the earlier one.
-  // A window is fetched in two parts, so that the page-table read can be in flight while other work goes on: the
-  // page id first, the addresses from it later.
-  auto window_page = [&](int w) __attribute__((always_inline)) {
-    const int gi = w * 64 + lane;
-    int page = -1;
-    if (gi * SKV_BLOCK_TOKENS < L && gi < p.max_blocks)
-      page = __builtin_nontemporal_load(&p.page_table[(size_t)r * p.max_blocks + gi]);
-    return page;
-  };
-  auto window_bases = [&](int w, int page, uint64_t& ak, uint64_t& av) __attribute__((always_inline)) {
-    const int gi = w * 64 + lane;
-    const int key0 = gi * SKV_BLOCK_TOKENS;
-    uint64_t k = (uint64_t)p.zero_page, v = k;
-    if (key0 < L) {
-      if (page >= 0 && page < p.n_pages) {
-        const uint64_t off = ((uint64_t)page * SKV_BLOCK_TOKENS * p.Hkv + kvh) * (kD * 2);
-        k = (uint64_t)p.kpool + off;
-        v = (uint64_t)p.vpool + off;
-      }
-    } else if (key0 < Ltot) {
-      const uint64_t off = ((uint64_t)(qbase + key0 - L) * p.Hkv + kvh) * (kD * 2);
-      k = (uint64_t)p.knew + off;
-      v = (uint64_t)p.vnew + off;
-    }
-    ak = k;
-    av = v;
-  };
-  auto fetch_window = [&](int w, uint64_t& ak, uint64_t& av) __attribute__((always_inline)) {
-    window_bases(w, window_page(w), ak, av);
-  };
   auto lane_bcast = [&](uint64_t x, int idx) __attribute__((always_inline)) {
     const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)x, idx);
     const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), idx);
@@ -314,8 +323,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   };
   uint64_t ak_cur, av_cur, ak_nxt, av_nxt;
   int win = 0;                       // window held in *_cur; *_nxt holds window win + 1
-  fetch_window(0, ak_cur, av_cur);
-  fetch_window(1, ak_nxt, av_nxt);
+  window_bases(0, page_w0, ak_cur, av_cur);
+  window_bases(1, page_w1, ak_nxt, av_nxt);
   typedef __attribute__((address_space(3))) void lds_void;
   // one pool (K or V) of tile t into an LDS stage; `bases` holds the window of tile t
   auto load_half_tile = [&](uint64_t bases, int t, __bf16* dst_stage) __attribute__((always_inline)) {
@@ -584,6 +593,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   load_k_tile(0, 0);
   if (n_tiles > 1) load_k_tile(1, 1);
   load_v_tile(0, 0);
+  stage_q();
   tile_barrier();
   const uint32_t k_base = lds_addr(Ks + k_lane), v_base = lds_addr(Vs + v_lane);
   constexpr uint32_t kStageBytes = kTile * 2, kHalfBytes = 8 * kSeg * 2;
