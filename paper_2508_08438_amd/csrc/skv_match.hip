@@ -19,6 +19,7 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kWavesPerWg = 4;
 constexpr int kSub = 4;                    // 256-token sub-windows per step: one 16-byte vector (4 tokens) per lane each
+constexpr int kFirstBlocks = 16;           // blocks the first round of a walk compares (one wavefront per request)
 constexpr int kStepBlocks = kSub * 16;     // 64 blocks (1024 tokens) per step: one block per lane for metadata and page ids
 constexpr int kAhead = 4;                  // steps of a node whose loads are in flight together
 constexpr int kCoopMaxRequests = 512;      // batches up to this size give every request a whole workgroup
@@ -120,11 +121,15 @@ __global__ __launch_bounds__(kWave* kWavesPerWg) void skv_match_kernel(
     const int nblk = uniform(nd.n_blocks);
     const int span = min(nblk, nb - j);  // blocks of this node the request can still cover
     const int jn = j;                    // request block that faces the node's first block
-    for (int r0 = 0; r0 < span && !stop; r0 += kRound) {
+    // With one wavefront per request (large batches) the very first round of a walk looks at kFirstBlocks blocks only:
+    // where sensitive blocks are frequent most walks end within a few blocks, and a full round would have fetched a
+    // few hundred blocks of the node for them.  A walk that gets past them pays one more round trip.
+    int width = (kCoop == 1 && j == 0) ? kFirstBlocks : kRound;
+    for (int r0 = 0; r0 < span && !stop; r0 += width, width = kRound) {
       // A node's span is contiguous, so the addresses of all steps are known at once: the loads of this wavefront's
       // kAhead steps (tokens of both sides, metadata, page ids) are issued together, then compared.
       const int g0 = r0 + wave * kGroup;            // first block (within the node) of this wavefront's group
-      const int g1 = min(span, g0 + kGroup);
+      const int g1 = min(span, g0 + (kCoop == 1 ? width : kGroup));
       tok4 a[kAhead][kSub], b[kAhead][kSub];
       int m[kAhead], pg[kAhead];   // per-block metadata word and page id of the lane's block
 #pragma unroll
