@@ -260,8 +260,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   const int page_w0 = window_page(0), page_w1 = window_page(1);
 
   // ---- Q fragments (B operand of S^T = K Q^T): lane holds query l32, d = 16 ks + 8 half .. +7
-  // Rows are fetched whole (16 lanes x 16 B per row), multiplied once by scale * log2(e) -- the scores then leave
-  // the matrix core in the units of exp2 -- and picked up from the wave's staging tile.
+  // Rows are fetched whole (16 lanes x 16 B per row) and picked up from the wave's staging tile.  The scores leave the
+  // matrix core unscaled; scale * log2(e) is applied in fp32 by the multiply-add that also subtracts the reference
+  // (scaling Q itself would round it to bf16 a second time: visible when scores spread over hundreds of units).
   const float c = p.scale * kLog2e;
   bf16x8 qf[8];
   u32x4 qv[8];
@@ -281,14 +282,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int rr = (lane >> 4) + 4 * i;    // row within the pass
-        u32x4 w;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const uint32_t x = qv[4 * pass + i][k];
-          f32x2 pr = {__builtin_bit_cast(float, x << 16) * c, __builtin_bit_cast(float, x & 0xffff0000u) * c};
-          w[k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
-        }
-        *(u32x4*)(stage + rr * kD + ((c16 ^ rr) << 3)) = w;
+        *(u32x4*)(stage + rr * kD + ((c16 ^ rr) << 3)) = qv[4 * pass + i];
       }
       if ((l32 >> 4) == pass) {
         const int rr = l32 & 15;
@@ -400,11 +394,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   // h on the vector ALU.  Nothing inside a half-step depends on anything else inside it, so its 16 MFMAs alternate
   // (score, output, score, ...) with two or three vector instructions behind each: the vector work runs beside the
   // MFMAs instead of between them.  Two score accumulators and two P^T buffers alternate.
-  f32x16 s[2];      // S^T of two consecutive sub-tiles: [32 keys][32 queries], in log2 units (Q carries the scale)
+  f32x16 s[2];      // S^T of two consecutive sub-tiles: [32 keys][32 queries], raw dot products
   bf16x8 pb[2][2];  // P^T as B operands: [sub-tile parity][16-key group]
   bf16x8 kfr[4];    // K fragment ring: runs four fragments ahead, across sub-tiles
   bf16x8 vfr[4];    // V^T fragment ring, likewise
-  float m_ref = 0.f;   // reference the exponentials are taken against (log2 units), per query
+  float m_ref = 0.f;   // reference the exponentials are taken against (score * scale * log2(e): exp2 units), per query
   float l_run = 0.f;   // running row sum over this lane-half's keys
 #pragma unroll
   for (int e = 0; e < 16; ++e) s[0][e] = s[1][e] = 0.f;
@@ -458,8 +452,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   bf16x8 pk;
   auto exp_pair = [&](const f32x16& cur, int i, bf16x8 (&p_make)[2], float& e0, float& e1, int part) __attribute__((always_inline)) {
     if (part == 0) {
-      e0 = __builtin_amdgcn_exp2f(cur[2 * i] - m_ref);
-      e1 = __builtin_amdgcn_exp2f(cur[2 * i + 1] - m_ref);
+      e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[2 * i], c, -m_ref));
+      e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[2 * i + 1], c, -m_ref));
     } else {
       f32x2 pr = {e0, e1};
       const bf16x2 cv = __builtin_convertvector(pr, bf16x2);
@@ -476,7 +470,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   // sub-tile's row maximum: O and the row sum are rescaled and this sub-tile's exponentials are taken again.  This
   // happens between half-steps, after the output update that still belongs to the old reference has been issued.
   auto move_reference = [&](const f32x16& cur, bf16x8 (&p_make)[2]) __attribute__((always_inline)) {
-    const float mx = row_max(cur);
+    const float mx = row_max(cur) * c;
     const bool trip = !(max_halves(ssum[0] + ssum[1]) <= kSumLimit);
     const float m_new = trip ? mx : m_ref;
     const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
@@ -513,7 +507,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
       lds_wait(11, kfr[i & 3]);
       dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[i & 3], qf[i], i == 0 ? zero16 : dst, 0, 0, 0);
       kfr[i & 3] = i < 4 ? k_frag(kb, i + 4) : k_frag(kb_next, i - 4);
-      const float f0 = __builtin_amdgcn_exp2f(cur[2 * i] - m_ref);
+      const float f0 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[2 * i], c, -m_ref));
       if (i > 0) {
         f32x2 pr = {e0, e1};
         const bf16x2 cv = __builtin_convertvector(pr, bf16x2);
@@ -525,7 +519,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
       lds_wait(10, vfr[i & 3]);
       o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[i & 3], p_use[i >> 2], o[i & 3], 0, 0, 0);
       vfr[i & 3] = i < 4 ? v_frag(vb, i + 4) : v_frag(vb_next, i - 4);
-      const float f1 = __builtin_amdgcn_exp2f(cur[2 * i + 1] - m_ref);
+      const float f1 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[2 * i + 1], c, -m_ref));
       if (i > 0) {
         ssum[1] += e1;
         if (((i - 1) & 3) == 3) p_make[(i - 1) >> 2] = pk;
@@ -614,7 +608,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
     // mask(), and the row maximum behind it would read score registers the matrix core has not written yet)
     asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+v"(s[0]));
     mask(s[0], 0);
-    m_ref = row_max(s[0]);   // finite: key 0 is visible to every query
+    m_ref = row_max(s[0]) * c;   // finite: key 0 is visible to every query
   }
 
   // ---- main loop.  Iteration kt (two half-steps) reads K(kt), K(kt + 1), V(kt - 1), V(kt).  It starts behind the

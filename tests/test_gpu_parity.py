@@ -306,6 +306,37 @@ def test_attention_shapes_and_ragged_edges(case):
     assert err <= (1e-4 if dtype == torch.float32 else 2e-2)
 
 
+def test_attention_reference_moves_under_large_scores():
+    """Scores with a spread of hundreds of log2 units (entries ~ N(0, 16)) over contexts long enough for the
+    pipelined loop (49 and 30 key tiles): the softmax reference has to move again and again, in the steady-state
+    loop as well as in the first and last iterations, and the result must still be the oracle's; then a ramp
+    (every key scores higher than all keys before it) that trips the reference in every sub-tile."""
+    c = attn_case(11, 2, 8, 2, 128, torch.bfloat16, 200, [150, 64], [190, 116], n_pages=320, sigma=4.0)
+    got = run_attn(c)
+    want = oracle.attention(c["q"], c["knew"], c["vnew"], c["q_off"], c["kpool"], c["vpool"], c["matched_len"],
+                            c["page_table"], n_threads=16)
+    err = np.abs(got - want)
+    print(f"   large scores: max-abs err {err.max():.3e} (|ref| max {np.abs(want).max():.3e})", flush=True)
+    assert np.isfinite(got).all() and err.max() <= 2e-2 * max(1.0, np.abs(want).max())
+    # ramp: K row j = (j / 4) * u, Q rows = u (unit-ish vector): score of key j grows by ~16 log2 units per 4 keys
+    g = np.random.default_rng(3)
+    u = g.standard_normal(128).astype(np.float32)
+    u *= 8.0 / np.linalg.norm(u)
+    c = attn_case(12, 1, 8, 2, 128, torch.bfloat16, 64, [128], [56], n_pages=64, sigma=1.0)
+    c["q"][:] = torch.from_numpy(u).to(torch.bfloat16)
+    L = int(c["matched_len"][0])
+    for j in range(L):
+        c["kpool"][c["page_table"][0, j // B], j % B] = torch.from_numpy(u * (j // 4)).to(torch.bfloat16)
+    for i in range(128):
+        c["knew"][i] = torch.from_numpy(u * ((L + i) // 4)).to(torch.bfloat16)
+    got = run_attn(c)
+    want = oracle.attention(c["q"], c["knew"], c["vnew"], c["q_off"], c["kpool"], c["vpool"], c["matched_len"],
+                            c["page_table"], n_threads=16)
+    err = np.abs(got - want)
+    print(f"   ramp: max-abs err {err.max():.3e} (|ref| max {np.abs(want).max():.3e})", flush=True)
+    assert np.isfinite(got).all() and err.max() <= 2e-2 * max(1.0, np.abs(want).max())
+
+
 def test_attention_closed_forms_on_gpu():
     """The oracle's closed-form pins, applied to the GPU path directly: V == 1 gives 1; K == 0 with
     V = position gives (L+i)/2 (bf16 holds integers up to 256 exactly)."""
