@@ -314,18 +314,20 @@ def main():
         h_ops = torch.from_numpy(chunk).to(torch.bfloat16).repeat((n_val >> 20) + 1)[:n_val]
         sink = torch.empty(skv.MFMA_RATE_SINK_BYTES // 4, dtype=torch.float32).to(sess.device)
         mfma_rate = {"kernel": "mfma_rate_kernel", "unit": "TFLOP/s", "instruction": "v_mfma_f32_32x32x16_bf16"}
-        for label, ops in (("workload_like_values", h_ops.to(sess.device)),
-                           ("constant_values", torch.ones(n_val, dtype=torch.bfloat16).to(sess.device))):
-            skv.skv_mfma_rate(ops, 40000, sink)            # the clock settles under load first
+        d_ops = h_ops.to(sess.device)
+        for label, ops, side in (("workload_like_values", d_ops, False),
+                                 ("workload_like_values_with_softmax_side_work", d_ops, True),
+                                 ("constant_values", torch.ones(n_val, dtype=torch.bfloat16).to(sess.device), False)):
+            skv.skv_mfma_rate(ops, 40000, sink, side_work=side)            # the clock settles under load first
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
             ev[0].record()
             for i in range(3):
-                fl = skv.skv_mfma_rate(ops, 40000, sink)
+                fl = skv.skv_mfma_rate(ops, 40000, sink, side_work=side)
                 ev[i + 1].record()
             torch.cuda.synchronize()
             ts = [ev[i].elapsed_time(ev[i + 1]) * 1e-3 for i in range(3)]
             mfma_rate[label] = fl / float(np.median(ts)) / 1e12
-        del h_ops, sink, ops
+        del h_ops, sink, ops, d_ops
 
     tokens = float(len(w.req_tokens))
     a = w.attn
@@ -368,6 +370,8 @@ def main():
         out["mfma_sustained"] = mfma_rate
         out["roofline"]["frac_of_sustained_mfma_rate_on_workload_like_values"] = (
             main_fig["attention_tflops"] / mfma_rate["workload_like_values"])
+        out["roofline"]["frac_of_sustained_rate_with_softmax_side_work"] = (
+            main_fig["attention_tflops"] / mfma_rate["workload_like_values_with_softmax_side_work"])
 
     # the counters after one step of this batch: what the safeguard would read (reuse statistics of the workload)
     hit, ucnt = sess.counters()

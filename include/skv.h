@@ -306,12 +306,16 @@ int skv_stream_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
  * against; constants give the nominal peak.  d_operands: DEVICE, at least SKV_MFMA_RATE_OPERAND_BYTES bytes of
  * bf16 values, 16-byte aligned (read once); d_sink: DEVICE, at least SKV_MFMA_RATE_SINK_BYTES bytes (overwritten,
  * keeps the results alive).  *flops (HOST, may be NULL) receives the floating-point operations one call issues;
- * the caller times the call on `stream`.
- * Errors: SKV_EINVAL for null or misaligned pointers or iters < 1; SKV_ENOMEM for buffers that are too small. */
+ * the caller times the call on `stream`.  side_work: 0 = the matrix instruction alone; 1 = every matrix
+ * instruction accompanied by what the softmax of skv_prefill_attn issues per matrix instruction at the least (its A
+ * operand read from LDS, one multiply-add, one exponential, one add, half a packed conversion) on values that
+ * depend on no matrix result, with no global load and no barrier: the rate that instruction mix can reach at all.
+ * Errors: SKV_EINVAL for null or misaligned pointers, iters < 1 or side_work other than 0 or 1; SKV_ENOMEM for
+ * buffers that are too small. */
 #define SKV_MFMA_RATE_OPERAND_BYTES ((size_t)512 * 512 * 6 * 32)
 #define SKV_MFMA_RATE_SINK_BYTES ((size_t)512 * 512 * 4)
-int skv_mfma_rate(const void* d_operands, size_t operand_bytes, int32_t iters, float* d_sink, size_t sink_bytes,
-                  double* flops, void* stream);
+int skv_mfma_rate(const void* d_operands, size_t operand_bytes, int32_t iters, int32_t side_work, float* d_sink,
+                  size_t sink_bytes, double* flops, void* stream);
 
 /* Bytes of device workspace skv_prefill_attn needs for n_req requests and at most
  * total_q_rows uncached tokens in the batch (the work list of the bf16 kernel and one page of zeros that

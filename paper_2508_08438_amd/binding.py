@@ -91,7 +91,7 @@ def lib():
                                               i32, vp, vp]
         l.skv_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
         l.skv_tree_compact.argtypes = [vp, vp, C.POINTER(i64), vp]
-        l.skv_mfma_rate.argtypes = [vp, C.c_size_t, i32, vp, C.c_size_t, C.POINTER(C.c_double), vp]
+        l.skv_mfma_rate.argtypes = [vp, C.c_size_t, i32, i32, vp, C.c_size_t, C.POINTER(C.c_double), vp]
         l.skv_match_limits_read.argtypes = [vp, C.POINTER(C.c_uint32), i32, vp]
         _lib = l
     return _lib
@@ -224,11 +224,12 @@ MFMA_RATE_OPERAND_BYTES = 512 * 512 * 6 * 32
 MFMA_RATE_SINK_BYTES = 512 * 512 * 4
 
 
-def skv_mfma_rate(operands: torch.Tensor, iters: int, sink: torch.Tensor, stream=None) -> float:
+def skv_mfma_rate(operands: torch.Tensor, iters: int, sink: torch.Tensor, stream=None, side_work: bool = False) -> float:
     """Enqueues the matrix-rate kernel; returns the floating-point operations it issues."""
     flops = C.c_double()
-    _check(lib().skv_mfma_rate(_dptr(operands), operands.numel() * operands.element_size(), iters, _dptr(sink),
-                               sink.numel() * sink.element_size(), C.byref(flops), _stream(stream)), "skv_mfma_rate")
+    _check(lib().skv_mfma_rate(_dptr(operands), operands.numel() * operands.element_size(), iters, int(side_work),
+                               _dptr(sink), sink.numel() * sink.element_size(), C.byref(flops), _stream(stream)),
+           "skv_mfma_rate")
     return flops.value
 
 

@@ -936,11 +936,16 @@ extern "C" int skv_prefill_attn_static(const skv_attn_desc* desc, int32_t n_req,
 // pairs of the caller's data in registers and issues the attention kernel's MFMA back to back into four
 // accumulators: no memory traffic, no other instructions.  One workgroup of eight wavefronts per compute unit; its
 // LDS claim keeps a second workgroup off the unit, so every SIMD runs exactly two wavefronts from start to end.
+// With side work, every MFMA is accompanied by what the attention kernel's softmax issues per MFMA at the least --
+// its A operand read from LDS (16 bytes per lane), one multiply-add, one exponential, one add and half a packed
+// conversion -- on values that depend on nothing the matrix core produces: no dependency on a result, no global
+// load, no barrier.  What this form sustains bounds any schedule of that instruction mix.
 namespace {
 constexpr int kRateMaxBlocks = 512, kRateThreads = 512, kRatePairs = 6, kRateLdsBytes = 96 * 1024;
+template <bool kSide>
 __global__ __launch_bounds__(kRateThreads) void mfma_rate_kernel(const u32x4* __restrict__ ops, float* __restrict__ sink,
                                                                  int iters) {
-  __shared__ uint32_t claim[kRateLdsBytes / 4];
+  __shared__ u32x4 claim[kRateLdsBytes / 16];
   const size_t lane_id = (size_t)blockIdx.x * kRateThreads + threadIdx.x;
   bf16x8 a[kRatePairs], b[kRatePairs];
 #pragma unroll
@@ -954,31 +959,67 @@ __global__ __launch_bounds__(kRateThreads) void mfma_rate_kernel(const u32x4* __
   for (int j = 0; j < 4; ++j)
 #pragma unroll
     for (int e = 0; e < 16; ++e) c[j][e] = 0.f;
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int j = 0; j < 16; ++j)
-      c[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j % kRatePairs], b[(j / 4 + j) % kRatePairs], c[j & 3], 0, 0, 0);
-  }
   float t = 0.f;
+  if (kSide) {
+    // the workgroup's own 96 KB of operand data fill the LDS; a wavefront reads A operands from its own 8 KB of it
+    constexpr int kVecs = kRateLdsBytes / 16;
+    for (int i = threadIdx.x; i < kVecs; i += kRateThreads) claim[i] = ops[(size_t)blockIdx.x * kVecs + i];
+    __syncthreads();
+    const uint32_t abase = lds_addr(&claim[(threadIdx.x & 63) + (threadIdx.x >> 6) * 512]);
+    bf16x8 ar[4] = {a[0], a[1], a[2], a[3]};   // ring: the read behind MFMA j serves MFMA j + 4
+    float x[4], e_prev = 0.f, e_pp = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) x[j] = (float)((threadIdx.x * 37 + j * 101) % 1000) * 0.001f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        lds_wait(3, ar[j & 3]);
+        c[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ar[j & 3], b[(j / 4 + j) % kRatePairs], c[j & 3], 0, 0, 0);
+        ar[j & 3] = lds_read_b128(abase, (j & 7) * 1024);
+        x[j & 3] = __builtin_fmaf(-1.9371f, __builtin_fabsf(x[j & 3]), 1.0f);   // bounded, never settles
+        const float e = __builtin_amdgcn_exp2f(x[j & 3]);
+        t += e_prev;                       // results are consumed one step late, as in the attention kernel: nothing
+        if (j & 1) {                       // waits for the transcendental unit
+          f32x2 pr = {e_pp, e_prev};
+          const bf16x2 cv = __builtin_convertvector(pr, bf16x2);
+          asm volatile("" ::"v"(cv));
+        }
+        e_pp = e_prev;
+        e_prev = e;
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    lds_wait(0, ar[0], ar[1], ar[2], ar[3]);
+  } else {
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        c[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j % kRatePairs], b[(j / 4 + j) % kRatePairs], c[j & 3], 0, 0, 0);
+    }
+  }
 #pragma unroll
   for (int j = 0; j < 4; ++j)
 #pragma unroll
     for (int e = 0; e < 16; ++e) t += c[j][e];
-  volatile uint32_t* used = claim;             // the array has to be used to be allocated
+  volatile uint32_t* used = (volatile uint32_t*)claim;   // the array has to be used to be allocated
   used[threadIdx.x] = __float_as_uint(t);
   sink[lane_id] = __uint_as_float(used[threadIdx.x]);
 }
 }  // namespace
 
-extern "C" int skv_mfma_rate(const void* d_operands, size_t operand_bytes, int32_t iters, float* d_sink,
-                             size_t sink_bytes, double* flops, void* stream) {
+extern "C" int skv_mfma_rate(const void* d_operands, size_t operand_bytes, int32_t iters, int32_t side_work,
+                             float* d_sink, size_t sink_bytes, double* flops, void* stream) {
   if (!d_operands || !d_sink || iters < 1 || ((uintptr_t)d_operands & 15)) return SKV_EINVAL;
+  if (side_work != 0 && side_work != 1) return SKV_EINVAL;
   if (operand_bytes < SKV_MFMA_RATE_OPERAND_BYTES || sink_bytes < SKV_MFMA_RATE_SINK_BYTES) return SKV_ENOMEM;
   int dev = 0, cus = 0;
   SKV_HIP(hipGetDevice(&dev));
   SKV_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   const int blocks = cus < kRateMaxBlocks ? cus : kRateMaxBlocks;
-  mfma_rate_kernel<<<blocks, kRateThreads, 0, (hipStream_t)stream>>>((const u32x4*)d_operands, d_sink, iters);
+  if (side_work)
+    mfma_rate_kernel<true><<<blocks, kRateThreads, 0, (hipStream_t)stream>>>((const u32x4*)d_operands, d_sink, iters);
+  else
+    mfma_rate_kernel<false><<<blocks, kRateThreads, 0, (hipStream_t)stream>>>((const u32x4*)d_operands, d_sink, iters);
   SKV_HIP(hipGetLastError());
   if (flops) *flops = (double)blocks * (kRateThreads / 64) * (double)iters * 16.0 * (2.0 * 32 * 32 * 16);
   return SKV_OK;

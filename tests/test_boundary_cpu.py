@@ -173,9 +173,10 @@ def test_limits_read_and_stream_copy_argument_checks(skv):
     v = C.c_uint32()
     assert l.skv_match_limits_read(None, C.byref(v), 1, None) == -1
     assert l.skv_tree_compact(None, None, None, None) == -1
-    assert l.skv_mfma_rate(None, 0, 1, None, 0, None, None) == -1
-    assert l.skv_mfma_rate(fake_ptr, 64, 1, fake_ptr, 64, None, None) == -2        # buffers too small
-    assert l.skv_mfma_rate(fake_ptr, 1 << 40, 0, fake_ptr, 1 << 40, None, None) == -1   # iters < 1
+    assert l.skv_mfma_rate(None, 0, 1, 0, None, 0, None, None) == -1
+    assert l.skv_mfma_rate(fake_ptr, 64, 1, 0, fake_ptr, 64, None, None) == -2     # buffers too small
+    assert l.skv_mfma_rate(fake_ptr, 1 << 40, 0, 0, fake_ptr, 1 << 40, None, None) == -1   # iters < 1
+    assert l.skv_mfma_rate(fake_ptr, 1 << 40, 1, 2, fake_ptr, 1 << 40, None, None) == -1   # side_work is 0 or 1
     fake = C.c_void_p(1 << 20)
     assert l.skv_stream_copy(fake, fake, 0, None) == 0                 # nothing to copy
     assert l.skv_stream_copy(None, fake, 64, None) == -1
