@@ -306,6 +306,38 @@ def test_attention_shapes_and_ragged_edges(case):
     assert err <= (1e-4 if dtype == torch.float32 else 2e-2)
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_matched_length_inside_a_block_counts_whole_blocks_only(dtype):
+    """A matched length that is not a multiple of 16 is rounded down to whole blocks by the gather and by both
+    attention kernels alike (Section 4.3.1: reuse is block granular): same result as with the rounded lengths."""
+    skv = _skv()
+    d = 128 if dtype == torch.bfloat16 else 64
+    S, k = [70, 33, 5], [3, 6, 1]
+    c = attn_case(41, len(S), 4, 2, d, dtype, max(k) + 1, S, k, sigma=1.0)
+    want = oracle.attention(**c, n_threads=8)
+    floor_len = c["matched_len"].copy()
+    c["matched_len"] = (floor_len + np.asarray([5, 15, 0], np.int32)).astype(np.int32)
+    got = run_attn(c)
+    err = np.abs(got[: want.shape[0]] - want).max()
+    print(f"   {dtype}: max-abs err {err:.3e}", flush=True)
+    assert err <= (1e-4 if dtype == torch.float32 else 2e-2)
+    dev = "cuda:0"
+    kp, vp = c["kpool"].to(dev), c["vpool"].to(dev)
+    ml, pt = torch.from_numpy(c["matched_len"]).to(dev), torch.from_numpy(c["page_table"]).to(dev)
+    total = int(floor_len.sum())
+    desc = skv.attn_desc(4, 2, d, dtype)
+    kctx = torch.full((total + 16,) + tuple(kp.shape[2:]), 7.0, dtype=dtype, device=dev)
+    vctx = torch.full_like(kctx, 7.0)
+    off = torch.zeros(len(S) + 1, dtype=torch.int64, device=dev)
+    skv.skv_gather_kv(desc, kp, vp, ml, pt, pt.shape[1], off, kctx, vctx)
+    torch.cuda.synchronize()
+    assert off.cpu().numpy().tolist() == np.concatenate([[0], np.cumsum(floor_len)]).tolist()
+    wk, wv = oracle.gather(c["kpool"], c["vpool"], floor_len, c["page_table"])
+    as_bytes = lambda t: t.contiguous().cpu().view(torch.uint8)
+    assert torch.equal(as_bytes(kctx[:total]), as_bytes(wk)) and torch.equal(as_bytes(vctx[:total]), as_bytes(wv))
+    assert float(kctx[total:].float().min()) == 7.0 and float(kctx[total:].float().max()) == 7.0   # nothing past the end
+
+
 def test_attention_reference_moves_under_large_scores():
     """Scores with a spread of hundreds of log2 units (entries ~ N(0, 16)) over contexts long enough for the
     pipelined loop (49 and 30 key tiles): the softmax reference has to move again and again, in the steady-state
