@@ -74,7 +74,9 @@ struct AttnParams {
 // that a workgroup of the attention kernel learns everything about its piece of work from one load.  A request's
 // heaviest (last) tile first.  The q tiles of a request are cut so that L + (first row of a tile) is a multiple of the
 // 64-key tile: the first tile is short when L is not, and every later tile ends exactly where a key tile ends, so
-// no workgroup streams a key tile for the sake of a few keys of round-up.
+// no workgroup streams a key tile for the sake of a few keys of round-up -- unless the short first tile makes the
+// request one tile longer than cutting from row 0 would and the reused prefix is long (L > S / 2): a tile more costs
+// a pass over about L + S / 2 keys, the round-up one more 64-key iteration in each of the S / 64 tiles.
 constexpr int kItemInts = 8;
 __global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_off,
                                      const int32_t* __restrict__ matched_len, int pos_per_wg,
@@ -94,6 +96,11 @@ __global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_of
       L = matched_len[r] > 0 ? matched_len[r] & ~(SKV_BLOCK_TOKENS - 1) : 0;   // whole blocks only
       head_rows = min(S, (kBN - L % kBN) % kBN);
       nt = S > 0 ? (head_rows > 0 ? 1 : 0) + (S - head_rows + pos_per_wg - 1) / pos_per_wg : 0;
+      const int nt_plain = (S + pos_per_wg - 1) / pos_per_wg;
+      if (nt_plain < nt && 2 * L > S) {   // the short first tile would cost a whole extra tile: cut from row 0 instead
+        head_rows = 0;
+        nt = nt_plain;
+      }
     }
     sh[threadIdx.x] = nt;
     __syncthreads();
