@@ -125,6 +125,7 @@ __global__ void attn_schedule_kernel(int n_req, const int32_t* __restrict__ q_of
         }
         rec[0] = make_int4(r, row0, qb, S);
         rec[1] = make_int4(L, row1, 0, 0);
+
       }
     }
     __syncthreads();
@@ -501,8 +502,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   // each MFMA with fragments 4..7 and then with fragments 0..3 of the following sub-tile.
   // Fast form (every stage at work, no masked key in sub-tile h): the 16 MFMAs alternate and carry the softmax between
   // them; a fragment is waited for four pair-steps after its request, with eleven (K) or ten (V^T) younger reads.
-  auto half_step_fast = [&](uint32_t kb, uint32_t kb_next, uint32_t vb, uint32_t vb_next, f32x16& dst, f32x16& cur,
-                            bf16x8 (&p_use)[2], bf16x8 (&p_make)[2]) __attribute__((always_inline)) {
+  auto half_step_fast = [&]<bool kMask>(int h, uint32_t kb, uint32_t kb_next, uint32_t vb, uint32_t vb_next, f32x16& dst,
+                                        f32x16& cur, bf16x8 (&p_use)[2], bf16x8 (&p_make)[2]) __attribute__((always_inline)) {
+    if (kMask) mask(cur, h);
     ssum[0] = ssum[1] = 0.f;
     // One exponential behind every MFMA, never two in a row: the transcendental unit takes about four issue slots
     // per instruction but works beside the issue port, so a second one right behind the first would hold the
@@ -624,8 +626,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   // tile; one more iteration than tiles, for the output update with the last sub-tile.
   // Iterations [1, kt_fast) of this wave have all three stages at work, no masked key and no ragged tile to load.
   const int kt_fast = min(min((L + pos0 - 63) / 64 + 1, (wave_key_end - 1) / 64), n_tiles - 3);
+  // Iterations [kt_fast, kt_mid) still have all three stages at work in both half-steps, but keys may be masked and
+  // the tiles they request may be ragged or absent (the last two or three before the diagonal tile): they run the
+  // fast form with the mask applied and the general loads.
+  const int kt_mid = (wave_key_end - 1) / 64;
   int st0 = 0;   // stage of K(kt) and V(kt); tile t sits in stage t % 3
-  auto iteration = [&]<bool kFast>(int kt) __attribute__((always_inline)) {
+  auto iteration = [&]<int kForm>(int kt) __attribute__((always_inline)) {   // 0 general, 1 fast, 2 fast with masks
+    constexpr bool kFast = kForm == 1;
     const int st1 = st0 == 2 ? 0 : st0 + 1;    // stage of tile kt + 1
     const int st2 = st1 == 2 ? 0 : st1 + 1;    // stage of tiles kt + 2 and kt - 1
     if (__builtin_expect(pend, 0)) {
@@ -638,10 +645,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
     const uint32_t kb1 = k_base + st1 * kStageBytes;   // K(kt + 1)
     const uint32_t vbp = v_base + st2 * kStageBytes;   // V(kt - 1)
     const uint32_t vb0 = v_base + st0 * kStageBytes;   // V(kt)
-    if (kFast) {
-      half_step_fast(kb0 + kHalfBytes, kb1, vbp + kHalfBytes, vb0, s[1], s[0], pb[1], pb[0]);
+    if (kForm == 1) {
+      half_step_fast.template operator()<false>(2 * kt, kb0 + kHalfBytes, kb1, vbp + kHalfBytes, vb0, s[1], s[0], pb[1], pb[0]);
       prep_bases(kt + 1);
-      half_step_fast(kb1, kb1 + kHalfBytes, vb0, vb0 + kHalfBytes, s[0], s[1], pb[0], pb[1]);
+      half_step_fast.template operator()<false>(2 * kt + 1, kb1, kb1 + kHalfBytes, vb0, vb0 + kHalfBytes, s[0], s[1], pb[0], pb[1]);
+    } else if (kForm == 2) {
+      half_step_fast.template operator()<true>(2 * kt, kb0 + kHalfBytes, kb1, vbp + kHalfBytes, vb0, s[1], s[0], pb[1], pb[0]);
+      prep_bases(kt + 1);
+      half_step_fast.template operator()<true>(2 * kt + 1, kb1, kb1 + kHalfBytes, vb0, vb0 + kHalfBytes, s[0], s[1], pb[0], pb[1]);
     } else {
       half_step_slow(2 * kt, kb0 + kHalfBytes, kb1, vbp + kHalfBytes, vb0, s[1], s[0], pb[1], pb[0]);
       prep_bases(kt + 1);
@@ -652,9 +663,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16_kernel(AttnParams p) {
   };
   int kt = 0;
   prep_bases(0);
-  iteration.template operator()<false>(kt++);
-  for (; kt < kt_fast; ++kt) iteration.template operator()<true>(kt);
-  for (; kt <= n_tiles; ++kt) iteration.template operator()<false>(kt);
+  iteration.template operator()<0>(kt++);
+  for (; kt < kt_fast; ++kt) iteration.template operator()<1>(kt);
+  for (; kt < kt_mid; ++kt) iteration.template operator()<2>(kt);
+  for (; kt <= n_tiles; ++kt) iteration.template operator()<0>(kt);
 
   // ---- normalise and store.  A lane holds query l32 with d = 32 a + 8 (e/4) + 4 half + e%4, i.e. sixteen 8-byte
   // pieces of one output row.  They go through the wave's staging tile, 16 rows at a time, and leave as whole
