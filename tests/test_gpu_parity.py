@@ -288,6 +288,9 @@ ATTN_SHAPES = [
     (4, 2, 128, torch.bfloat16, [300, 5, 129], [2, 11, 0]),                       # G=2: 2 heads x 2 position tiles
     (3, 3, 128, torch.bfloat16, [257, 1, 64], [0, 5, 8]),                         # G=1: 4 position tiles
     (16, 8, 128, torch.bfloat16, [70, 33], [3, 6]),                               # Hkv=8: per-XCD head placement
+    (16, 1, 128, torch.bfloat16, [70, 33, 129], [3, 6, 0]),                       # G=16: four head groups
+    (3, 1, 128, torch.bfloat16, [300, 33], [1, 6]),                               # G=3: one head, 8 position tiles of 32
+    (12, 2, 128, torch.bfloat16, [140, 20], [5, 2]),                              # G=6: 2 heads x 4 position tiles, 3 groups
     (4, 2, 64, torch.float32, [1, 50, 0, 70], [0, 2, 3, 6]),
     (2, 1, 128, torch.float32, [40, 9], [1, 4]),
 ]
